@@ -1,0 +1,204 @@
+"""CPU oracle for the structured-sparse SAM encoder block -- TEST INFRASTRUCTURE.
+
+Thin ctypes/numpy marshalling over ``libssam_oracle.so`` (built from
+``ssam_oracle.c`` in this folder with gcc).  Nothing here is a product path and
+nothing here imports the HIP library or its binding.  Only tests, the smoke
+check and the benchmark's ``cpu_baseline`` leg may import this package.
+
+Every function cites the passage of the paper (arXiv 2605.17633) it follows in
+the C source; this file only moves arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libssam_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle's C source with gcc (``make`` in this folder)."""
+    src = os.path.join(_HERE, "ssam_oracle.c")
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
+        subprocess.run(["make", "-B", "-C", _HERE], check=True, capture_output=True)
+    return _SO
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_SO)
+    return _lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise ValueError(f"{name} failed with code {rc}")
+
+
+def morton_order(gh: int, gw: int) -> np.ndarray:
+    pi = np.empty(gh * gw, np.int32)
+    _check(lib().oracle_morton_order(C.c_int(gh), C.c_int(gw), _p(pi)), "oracle_morton_order")
+    return pi
+
+
+def stripe_sort(pi: np.ndarray, G: int):
+    pi = _i32(pi)
+    sigma = np.empty_like(pi)
+    sinv = np.empty_like(pi)
+    _check(lib().oracle_stripe_sort(_p(pi), C.c_int(pi.size), C.c_int(G), _p(sigma), _p(sinv)),
+           "oracle_stripe_sort")
+    return sigma, sinv
+
+
+def grid_sigma(w: int, G: int):
+    return stripe_sort(morton_order(w, w), G)
+
+
+def window_table(g: int, ws: int, G: int) -> np.ndarray:
+    nws = (g + ws - 1) // ws
+    t = np.empty(nws * nws * ws * ws, np.int32)
+    _check(lib().oracle_window_table(C.c_int(g), C.c_int(ws), C.c_int(G), _p(t)), "oracle_window_table")
+    return t
+
+
+def block_mask(S: int, Bm: int, r: float):
+    T = (S + Bm - 1) // Bm
+    m = np.empty((T, T), np.uint8)
+    n_pre = C.c_int(0)
+    _check(lib().oracle_block_mask(C.c_int(S), C.c_int(Bm), C.c_double(r), _p(m), C.byref(n_pre)),
+           "oracle_block_mask")
+    return m, n_pre.value
+
+
+def attention(q, k, v, rel_h, rel_w, w: int, G: int, Bm: int, r: float, sinv=None) -> np.ndarray:
+    """q,k,v [h,S,d] in spatial order, S = w*w; returns [h,S,d] in spatial order."""
+    q, k, v, rel_h, rel_w = map(_f32, (q, k, v, rel_h, rel_w))
+    h, S, d = q.shape
+    assert S == w * w and k.shape == q.shape and v.shape == q.shape
+    assert rel_h.shape == (2 * w - 1, d) and rel_w.shape == (2 * w - 1, d)
+    out = np.empty_like(q)
+    if sinv is None:
+        rc = lib().oracle_attention(_p(q), _p(k), _p(v), _p(rel_h), _p(rel_w), C.c_int(h), C.c_int(w),
+                                    C.c_int(d), C.c_int(G), C.c_int(Bm), C.c_double(r), _p(out))
+    else:
+        sinv = _i32(sinv)
+        assert sinv.size == S
+        rc = lib().oracle_attention_ordered(_p(q), _p(k), _p(v), _p(rel_h), _p(rel_w), C.c_int(h),
+                                            C.c_int(w), C.c_int(d), _p(sinv), C.c_int(Bm),
+                                            C.c_double(r), _p(out))
+    _check(rc, "oracle_attention")
+    return out
+
+
+def score_tokens(x) -> np.ndarray:
+    """x [gh,gw,D] -> M [gh,gw] (Eq. 1)."""
+    x = _f32(x)
+    gh, gw, D = x.shape
+    M = np.empty((gh, gw), np.float32)
+    _check(lib().oracle_score_tokens(_p(x), C.c_int(gh), C.c_int(gw), C.c_int(D), _p(M)),
+           "oracle_score_tokens")
+    return M
+
+
+def keep_count(n: int, rho: float) -> int:
+    K = lib().oracle_keep_count(C.c_int(n), C.c_double(rho))
+    if K < 0:
+        raise ValueError("oracle_keep_count: bad argument")
+    return K
+
+
+def select_tokens(scores, K: int) -> np.ndarray:
+    scores = _f32(scores).reshape(-1)
+    keep = np.empty(K, np.int32)
+    _check(lib().oracle_select_tokens(_p(scores), C.c_int(scores.size), C.c_int(K), _p(keep)),
+           "oracle_select_tokens")
+    return keep
+
+
+def routed_mlp(x, keep, ln_g, ln_b, w1, b1, w2, b2, eps: float = 1e-6) -> np.ndarray:
+    """x [n,D]; returns the updated copy."""
+    x = _f32(x).copy()
+    n, D = x.shape
+    keep = _i32(keep)
+    ln_g, ln_b, w1, b1, w2, b2 = map(_f32, (ln_g, ln_b, w1, b1, w2, b2))
+    Dm = w1.shape[0]
+    assert w1.shape == (Dm, D) and w2.shape == (D, Dm)
+    _check(lib().oracle_routed_mlp(_p(x), C.c_int(n), C.c_int(D), C.c_int(Dm), _p(keep), C.c_int(keep.size),
+                                   _p(ln_g), _p(ln_b), C.c_double(eps), _p(w1), _p(b1), _p(w2), _p(b2)),
+           "oracle_routed_mlp")
+    return x
+
+
+@dataclass
+class BlockWeights:
+    """fp32 arrays (values already rounded to bf16 by the generator)."""
+    ln1_g: np.ndarray
+    ln1_b: np.ndarray
+    wqkv: np.ndarray     # [3D, D]
+    bqkv: np.ndarray     # [3D]
+    rel_h: np.ndarray    # [2w-1, d]
+    rel_w: np.ndarray    # [2w-1, d]
+    wproj: np.ndarray    # [D, D]
+    bproj: np.ndarray    # [D]
+    ln2_g: np.ndarray
+    ln2_b: np.ndarray
+    w1: np.ndarray       # [Dm, D]
+    b1: np.ndarray
+    w2: np.ndarray       # [D, Dm]
+    b2: np.ndarray
+
+
+def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: float = 1e-6) -> np.ndarray:
+    """x [g,g,D] one image; ws = 0 for a global block.  Returns the block output."""
+    x = _f32(x).copy()
+    g, g2, D = x.shape
+    assert g == g2
+    keep = _i32(keep)
+    a = {f: _f32(getattr(wt, f)) for f in wt.__dataclass_fields__}
+    Dm = a["w1"].shape[0]
+    w = ws if ws > 0 else g
+    d = D // h
+    assert a["rel_h"].shape == (2 * w - 1, d), (a["rel_h"].shape, w, d)
+    rc = lib().oracle_encoder_block(
+        _p(x), C.c_int(g), C.c_int(D), C.c_int(h), C.c_int(Dm), C.c_int(ws), C.c_int(G), C.c_int(Bm),
+        C.c_double(r), _p(keep), C.c_int(keep.size), C.c_double(eps),
+        _p(a["ln1_g"]), _p(a["ln1_b"]), _p(a["wqkv"]), _p(a["bqkv"]), _p(a["rel_h"]), _p(a["rel_w"]),
+        _p(a["wproj"]), _p(a["bproj"]), _p(a["ln2_g"]), _p(a["ln2_b"]),
+        _p(a["w1"]), _p(a["b1"]), _p(a["w2"]), _p(a["b2"]))
+    _check(rc, "oracle_encoder_block")
+    return x
+
+
+def encoder(x, blocks, h: int, ws: int, global_blocks, G: int, r: float, rho: float,
+            Bm_window: int = 32, Bm_global: int = 128, eps: float = 1e-6):
+    """One image through a stack of blocks (Sec. 4: scores and keep-set are taken
+    once, from the encoder input, and reused by every block).  Returns (y, keep)."""
+    x = _f32(x)
+    g = x.shape[0]
+    K = keep_count(g * g, rho)
+    keep = select_tokens(score_tokens(x), K)
+    for i, wt in enumerate(blocks):
+        is_global = i in global_blocks
+        x = encoder_block(x, wt, h, 0 if is_global else ws, G, Bm_global if is_global else Bm_window,
+                          r, keep, eps)
+    return x, keep
