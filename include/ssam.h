@@ -1,0 +1,240 @@
+/*
+ * ssam.h -- C ABI of the MI355X (gfx950) structured-sparse SAM ViT encoder block
+ * of "SparseSAM" (arXiv 2605.17633): Stripe-Sort Attention (Sec. 4.1, App. A.1
+ * Alg. 1) and the Residual-Consistency MLP (Sec. 4.2).
+ *
+ * Conventions (all entry points)
+ *   - Return value: SSAM_OK (0) or a negative ssam_status.  Nothing throws or
+ *     aborts.  A failed argument check enqueues nothing.
+ *   - Ownership: the caller owns every buffer, including workspaces and index
+ *     tables.  Unless a call's comment says otherwise the library allocates no
+ *     device memory, keeps no global mutable state and never synchronises: it
+ *     only enqueues kernels on the caller's stream.
+ *   - "dev" = device (HBM) pointer, "host" = host pointer.  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Tensors are dense, row-major.  Activations and Linear weights are bf16
+ *     (16-bit, upper half of an IEEE fp32); LayerNorm parameters, Linear biases
+ *     and token scores are fp32; indices are int32.  Device pointers must be
+ *     16-byte aligned, feature widths multiples of 8.
+ *   - Linear weights use the [out, in] layout (y = x W^T + b).
+ *   - bf16 arithmetic: products are exact, sums are fp32, every tensor written
+ *     to memory is rounded to bf16 (nearest even) once.
+ */
+#ifndef SSAM_H
+#define SSAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ssam_status {
+    SSAM_OK = 0,
+    SSAM_EINVAL = -1,       /* null / misaligned pointer, size or density out of range */
+    SSAM_EUNSUPPORTED = -2, /* a shape the kernels are not built for                   */
+    SSAM_EWORKSPACE = -3,   /* workspace smaller than the matching *_workspace_bytes   */
+    SSAM_EHIP = -4          /* a HIP runtime call (launch, attribute) failed           */
+} ssam_status;
+
+/* Static string for a status code. */
+const char *ssam_status_string(int status);
+
+/* ------------------------------------------------------------------------- */
+/* Integer layout layer (one-time; Sec. 4.1 "precomputed once")              */
+/* ------------------------------------------------------------------------- */
+
+/* Stripe-Sort scan order of a gh x gw token grid (Fig. 2 caption; Sec. 4.1).
+ * pi = Z-order (Morton) traversal: cells ranked by the bit-interleaved code in
+ * which the column supplies the even bits and the row the odd bits.
+ * perm = sigma = flatten(T^T), T[t][g] = pi[t*G+g]  (G = 1: perm = pi).
+ * perm[p] = row-major cell index at scan position p; inv[perm[p]] = p.
+ * perm, inv: host, gh*gw int32 each; inv may be NULL.
+ * SSAM_EINVAL: non-positive sizes, G < 1, gh*gw not divisible by G. */
+int ssam_build_perm(int gh, int gw, int G, int32_t *perm, int32_t *inv);
+
+/* The same table computed by a HIP kernel straight into device memory
+ * (perm_dev, inv_dev: dev, gh*gw int32; inv_dev may be NULL).  gh, gw <= 1024. */
+int ssam_build_perm_device(int gh, int gw, int G, int32_t *perm_dev, int32_t *inv_dev, void *stream);
+
+/* Window-major gather table (App. A.1 "window-major -> spatial perms"): the
+ * g x g grid is padded to nws*ws per side, nws = ceil(g/ws), and cut into
+ * ws x ws windows; inside a window tokens follow ssam_build_perm(ws, ws, G).
+ * table[(wr*nws+wc)*ws*ws + p] = row*g+col of the token at scan position p of
+ * window (wr,wc), or -1 for a padding cell.  table: host, nws*nws*ws*ws int32. */
+int ssam_build_window_table(int g, int ws, int G, int32_t *table);
+
+/* A-shape block mask of Alg. 1 in CSR form.  T = ceil(S/mask_block) tiles per
+ * side, n_pre = floor(r*T) (double, +1e-6 guard, clamped to [0,T]); row tile i
+ * lists column tiles 0..n_pre-1 and, if i >= n_pre, its diagonal tile i.
+ * row_ptr: host, T+1 int32.  col_idx: host, room for T*T int32 (ascending in
+ * each row).  n_pre: host, optional.  SSAM_EINVAL unless 0 < r <= 1. */
+int ssam_build_block_mask(int S, int mask_block, double r, int32_t *row_ptr, int32_t *col_idx, int *n_pre);
+
+/* Keep count of the routed MLP (Sec. 4.2): clamp(floor(rho*N + 1e-6), 1, N);
+ * negative status on bad arguments. */
+int ssam_keep_count(int N, double rho);
+
+/* ------------------------------------------------------------------------- */
+/* HBM-bound movers                                                          */
+/* ------------------------------------------------------------------------- */
+
+/* Row gather (Sec. 4.1: reorder tokens by the scan order):
+ * y[b][p][:] = idx[p] >= 0 ? x[b][idx[p]][:] : 0.
+ * x dev bf16 [B][Nin][D]; idx dev int32 [Nout], each < Nin; y dev bf16 [B][Nout][D]. */
+int ssam_permute(const void *x, const int32_t *idx, void *y, int B, int Nin, int Nout, int D, void *stream);
+
+/* Inverse scatter: x[b][idx[p]][:] = y[b][p][:] (+ residual[b][idx[p]][:] when
+ * residual != NULL) for idx[p] >= 0.  idx must not repeat a row.  Rows of x no
+ * idx names are left untouched.  residual may alias x. */
+int ssam_unpermute(const void *y, const int32_t *idx, void *x, const void *residual,
+                   int B, int Nx, int Ny, int D, void *stream);
+
+/* Fused pre-LayerNorm + gather (block input path; also gathers the keep-set
+ * for the routed MLP): y[b][p][:] = LN(x[b][idx[b*idx_batch_stride+p]][:]) with
+ * biased variance, fp32 statistics; idx < 0 gives a zero row.
+ * idx_batch_stride = 0 shares one table over the batch.  gamma, beta dev fp32 [D]. D <= 2048. */
+int ssam_ln_gather(const void *x, const int32_t *idx, int idx_batch_stride,
+                   const float *gamma, const float *beta, float eps, void *y,
+                   int B, int Nin, int Nout, int D, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Dense contraction (the block's qkv / proj / fc1 / fc2 layers)             */
+/* ------------------------------------------------------------------------- */
+
+typedef enum ssam_epilogue {
+    SSAM_EPI_BIAS = 0,        /* C = A W^T + b                                         */
+    SSAM_EPI_BIAS_GELU = 1,   /* C = gelu_erf(A W^T + b)                               */
+    SSAM_EPI_BIAS_SCATTER_ADD = 2 /* C[dst(m)] += A W^T + b, dst from a row map (below) */
+} ssam_epilogue;
+
+/* C = epilogue(A W^T + bias).  A dev bf16 [M][K]; W dev bf16 [N][K]; bias dev
+ * fp32 [N]; C dev bf16.  N % 128 == 0 and K % 64 == 0 (else SSAM_EUNSUPPORTED).
+ * SSAM_EPI_BIAS_SCATTER_ADD: row m = b*rows_per_batch + p of the product is
+ * added into row b*dst_rows_per_batch + row_map[b*map_batch_stride + p] of C
+ * (skipped where the map is negative); C holds the residual stream and is
+ * updated in place: new = bf16(old + acc + bias).  The map must not repeat a
+ * row within a batch item.  Other epilogues ignore the map arguments and write
+ * C [M][N]. */
+int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
+                int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
+                int dst_rows_per_batch, void *stream);
+
+/* The same with the workgroup tile forced (tuning and tests): tile = 0 picks
+ * automatically, 1 = 256x256 (needs N % 256 == 0), 2 = 256x128, 3 = 128x128. */
+int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
+                      int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
+                      int dst_rows_per_batch, int tile, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Stripe-Sort attention (App. A.1, Alg. 1)                                  */
+/* ------------------------------------------------------------------------- */
+
+/* For every group g (a window, or a whole image for global blocks) and head:
+ *   O = softmax_over_active_tiles(scale * Q K^T + B) V
+ * with tokens already in scan order.  Active key tiles of query tile i:
+ * {0..floor(r*T)-1} U {i}, tiles of mask_block tokens, T = ceil(S/mask_block).
+ * B[p][p'] = q_p . rel_h[row(p)-row(p')+w-1] + q_p . rel_w[col(p)-col(p')+w-1]
+ * (unscaled q), (row, col) = divmod(sigma[p], w): sigma maps scan position ->
+ * spatial cell of the w x w grid, S = w*w.
+ *   q, k, v  dev bf16; element (g, p, head, c) at ptr[(g*S+p)*row_stride + head*d + c]
+ *            (a packed [groups][S][3][h][d] buffer: row_stride = 3*h*d, k = q + h*d, v = q + 2*h*d)
+ *   rel_h, rel_w  dev bf16 [(2w-1)][d]      sigma  dev int32 [S]
+ *   out      dev bf16 [groups][S][h*d]
+ * Built for d in {64, 80} (d % 16 == 0, d <= 96 accepted), mask_block = 32 with
+ * S <= 224 (windows) and mask_block = 128 with S <= 16384 (global); otherwise
+ * SSAM_EUNSUPPORTED. */
+int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,
+                          const void *rel_h, const void *rel_w, const int32_t *sigma, void *out,
+                          int groups, int S, int w, int h, int d, int mask_block, double r,
+                          float scale, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Residual-Consistency MLP (Sec. 4.2)                                       */
+/* ------------------------------------------------------------------------- */
+
+/* Token scores of Eq. 1: Sobel gradient magnitude (zero padding) of the map
+ * summed over channels.  x dev bf16 [B][gh][gw][D]; scores dev fp32 [B][gh*gw];
+ * workspace dev, >= ssam_score_tokens_workspace_bytes. */
+size_t ssam_score_tokens_workspace_bytes(int B, int gh, int gw);
+int ssam_score_tokens(const void *x, float *scores, int B, int gh, int gw, int D,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Keep-set: per batch item the K highest scores, ties to the lower index
+ * (-0.0 == +0.0; NaN ranks as -inf), written in ascending index order.
+ * scores dev fp32 [B][N]; keep_idx dev int32 [B][K]; 1 <= K <= N <= 65536. */
+int ssam_select_tokens(const float *scores, int32_t *keep_idx, int B, int N, int K, void *stream);
+
+/* x[b][i] += W2 gelu_erf(W1 LN(x[b][i]) + b1) + b2 for i in keep_idx[b][:];
+ * every other row of x is never written (bit-identical).
+ * x dev bf16 [B][N][D] in place; keep_idx dev int32 [B][K], distinct per b,
+ * in [0,N) (contract; not checked on device).  w1 [Dm][D], w2 [D][Dm] bf16;
+ * b1 [Dm], b2 [D], ln_g, ln_b [D] fp32. */
+size_t ssam_routed_mlp_workspace_bytes(int B, int K, int D, int Dm);
+int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                    const void *w1, const float *b1, const void *w2, const float *b2,
+                    int B, int N, int D, int Dm, int K,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Encoder block and stack                                                   */
+/* ------------------------------------------------------------------------- */
+
+typedef struct ssam_block_weights {     /* every pointer: dev */
+    const float *ln1_g, *ln1_b;         /* [D] fp32                                  */
+    const void *wqkv;                   /* bf16 [3D][D], out channel = which*D+head*d+c */
+    const float *bqkv;                  /* [3D] fp32                                 */
+    const void *rel_h, *rel_w;          /* bf16 [(2w-1)][d], w = ws (local) or g (global) */
+    const void *wproj;                  /* bf16 [D][D]                               */
+    const float *bproj;                 /* [D] fp32                                  */
+    const float *ln2_g, *ln2_b;         /* [D] fp32                                  */
+    const void *w1;                     /* bf16 [Dm][D]                              */
+    const float *b1;                    /* [Dm] fp32                                 */
+    const void *w2;                     /* bf16 [D][Dm]                              */
+    const float *b2;                    /* [D] fp32                                  */
+} ssam_block_weights;
+
+typedef struct ssam_block_cfg {
+    int B;            /* images                                                  */
+    int g;            /* token grid side (N = g*g)                               */
+    int D, heads, Dm; /* width, heads (d = D/heads), MLP hidden width            */
+    int ws;           /* window side; 0 = global attention over the whole grid   */
+    int mask_block;   /* A-shape tile: 32 for windows, 128 for global            */
+    int K;            /* kept tokens per image for the routed MLP                */
+    double r;         /* attention density in (0,1]                              */
+    float eps;        /* LayerNorm epsilon                                       */
+} ssam_block_cfg;
+
+/* One structured-sparse block, in place on x dev bf16 [B][g][g][D]:
+ *   u = LN1(x) gathered into scan order (windows: zero rows for padding)
+ *   qkv = u Wqkv^T + b;  o = Stripe-Sort attention;  x += scatter(o Wproj^T + b)
+ *   routed MLP over keep_idx.
+ * gather_table dev int32: ws > 0: ssam_build_window_table(g, ws, G) (nws*nws*ws*ws);
+ *                         ws = 0: ssam_build_perm(g, g, G) (g*g).
+ * sigma dev int32 [S]: ssam_build_perm(w, w, G) of one attention group.
+ * keep_idx dev int32 [B][K].  workspace >= ssam_encoder_block_workspace_bytes(cfg). */
+size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg);
+int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
+                       const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* A stack of blocks on one batch (Sec. 1: one static permutation set and one
+ * keep-set, computed once, reused by every layer): scores (Eq. 1) and the
+ * keep-set are taken from the input x, then block i runs with cfg_local or,
+ * where is_global[i] != 0, cfg_global.  weights, is_global: host arrays of
+ * n_blocks entries.  keep_idx dev int32 [B][K] is written and then read;
+ * scores dev fp32 [B][N] likewise.  Tables as for ssam_encoder_block.
+ * workspace >= ssam_encoder_workspace_bytes(cfg_local, cfg_global). */
+size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global);
+int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
+                         const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,
+                         const int32_t *window_table, const int32_t *sigma_window,
+                         const int32_t *global_table, const int32_t *sigma_global,
+                         float *scores, int32_t *keep_idx,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSAM_H */

@@ -1,0 +1,288 @@
+"""Python binding of libssam (argument marshalling only).
+
+Every function has the name of the C entry point in ``include/ssam.h`` and does
+nothing but check dtypes, pull raw pointers out of torch tensors and forward
+them with the current torch stream.  No step of the method runs in Python or in
+PyTorch ops.  If the HIP library has not been built the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssam.so")
+_lib = None
+
+EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_SCATTER_ADD = 0, 1, 2
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+
+
+class SsamError(RuntimeError):
+    def __init__(self, name, code):
+        self.code = code
+        super().__init__(f"{name}: {status_string(code)} ({code})")
+
+
+class BlockWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj", "bproj",
+        "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")]
+
+
+class BlockCfg(C.Structure):
+    _fields_ = [("B", C.c_int), ("g", C.c_int), ("D", C.c_int), ("heads", C.c_int), ("Dm", C.c_int),
+                ("ws", C.c_int), ("mask_block", C.c_int), ("K", C.c_int), ("r", C.c_double), ("eps", C.c_float)]
+
+
+def lib():
+    """Load libssam.so; fail loudly if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.ssam_status_string.restype = C.c_char_p
+        for n in ("ssam_score_tokens_workspace_bytes", "ssam_routed_mlp_workspace_bytes",
+                  "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes"):
+            getattr(L, n).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().ssam_status_string(C.c_int(code)).decode()
+
+
+def _check(name, rc):
+    if rc != 0:
+        raise SsamError(name, rc)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return C.c_void_p(0)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous device tensor of {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+_bf = lambda t, n: _dev(t, torch.bfloat16, n)
+_f32 = lambda t, n: _dev(t, torch.float32, n)
+_i32 = lambda t, n: _dev(t, torch.int32, n)
+
+
+# ------------------------------------------------------------------ integer layer (host)
+def ssam_build_perm(gh: int, gw: int, G: int):
+    perm = np.empty(gh * gw, np.int32)
+    inv = np.empty(gh * gw, np.int32)
+    _check("ssam_build_perm", lib().ssam_build_perm(C.c_int(gh), C.c_int(gw), C.c_int(G),
+                                                    perm.ctypes.data_as(C.c_void_p), inv.ctypes.data_as(C.c_void_p)))
+    return perm, inv
+
+
+def ssam_build_perm_device(gh: int, gw: int, G: int, device="cuda"):
+    perm = torch.empty(max(gh * gw, 1), dtype=torch.int32, device=device)
+    inv = torch.empty_like(perm)
+    _check("ssam_build_perm_device", lib().ssam_build_perm_device(C.c_int(gh), C.c_int(gw), C.c_int(G),
+                                                                  _i32(perm, "perm"), _i32(inv, "inv"), _stream()))
+    return perm, inv
+
+
+def ssam_build_window_table(g: int, ws: int, G: int):
+    nws = (g + ws - 1) // ws
+    t = np.empty(nws * nws * ws * ws, np.int32)
+    _check("ssam_build_window_table", lib().ssam_build_window_table(C.c_int(g), C.c_int(ws), C.c_int(G),
+                                                                    t.ctypes.data_as(C.c_void_p)))
+    return t
+
+
+def ssam_build_block_mask(S: int, mask_block: int, r: float):
+    T = (S + mask_block - 1) // mask_block
+    row_ptr = np.empty(T + 1, np.int32)
+    col_idx = np.empty(T * T, np.int32)
+    n_pre = C.c_int(0)
+    _check("ssam_build_block_mask", lib().ssam_build_block_mask(
+        C.c_int(S), C.c_int(mask_block), C.c_double(r), row_ptr.ctypes.data_as(C.c_void_p),
+        col_idx.ctypes.data_as(C.c_void_p), C.byref(n_pre)))
+    return row_ptr, col_idx[: row_ptr[-1]].copy(), n_pre.value
+
+
+def ssam_keep_count(N: int, rho: float) -> int:
+    K = lib().ssam_keep_count(C.c_int(N), C.c_double(rho))
+    if K < 0:
+        raise SsamError("ssam_keep_count", K)
+    return K
+
+
+# ------------------------------------------------------------------ movers
+def ssam_permute(x, idx, y=None):
+    B, Nin, D = x.shape
+    Nout = idx.numel()
+    if y is None:
+        y = torch.empty((B, Nout, D), dtype=torch.bfloat16, device=x.device)
+    _check("ssam_permute", lib().ssam_permute(_bf(x, "x"), _i32(idx, "idx"), _bf(y, "y"), C.c_int(B), C.c_int(Nin),
+                                              C.c_int(Nout), C.c_int(D), _stream()))
+    return y
+
+
+def ssam_unpermute(y, idx, x, residual=None):
+    B, Ny, D = y.shape
+    Nx = x.shape[1]
+    _check("ssam_unpermute", lib().ssam_unpermute(_bf(y, "y"), _i32(idx, "idx"), _bf(x, "x"), _bf(residual, "residual"),
+                                                  C.c_int(B), C.c_int(Nx), C.c_int(Ny), C.c_int(D), _stream()))
+    return x
+
+
+def ssam_ln_gather(x, idx, idx_batch_stride, gamma, beta, eps, Nout, y=None):
+    B, Nin, D = x.shape
+    if y is None:
+        y = torch.empty((B, Nout, D), dtype=torch.bfloat16, device=x.device)
+    _check("ssam_ln_gather", lib().ssam_ln_gather(_bf(x, "x"), _i32(idx, "idx"), C.c_int(idx_batch_stride),
+                                                  _f32(gamma, "gamma"), _f32(beta, "beta"), C.c_float(eps), _bf(y, "y"),
+                                                  C.c_int(B), C.c_int(Nin), C.c_int(Nout), C.c_int(D), _stream()))
+    return y
+
+
+# ------------------------------------------------------------------ GEMM
+def ssam_linear(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows_per_batch=1, map_batch_stride=0,
+                dst_rows_per_batch=1, tile=0):
+    M, K = A.shape
+    N = W.shape[0]
+    assert W.shape[1] == K
+    if C_out is None:
+        C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    _check("ssam_linear", lib().ssam_linear_tiled(
+        _bf(A, "A"), _bf(W, "W"), _f32(bias, "bias"), _bf(C_out, "C"), C.c_int(M), C.c_int(N), C.c_int(K),
+        C.c_int(epilogue), _i32(row_map, "row_map"), C.c_int(rows_per_batch), C.c_int(map_batch_stride),
+        C.c_int(dst_rows_per_batch), C.c_int(tile), _stream()))
+    return C_out
+
+
+# ------------------------------------------------------------------ attention
+def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None, out=None):
+    """qkv: packed [groups, S, 3, h, d] bf16.  Returns [groups, S, h*d]."""
+    groups, S, three, h, d = qkv.shape
+    assert three == 3
+    if out is None:
+        out = torch.empty((groups, S, h * d), dtype=torch.bfloat16, device=qkv.device)
+    if scale is None:
+        scale = d ** -0.5
+    base = qkv.data_ptr()
+    _bf(qkv, "qkv")
+    esz = 2
+    _check("ssam_sparse_attention", lib().ssam_sparse_attention(
+        C.c_void_p(base), C.c_void_p(base + h * d * esz), C.c_void_p(base + 2 * h * d * esz), C.c_long(3 * h * d),
+        _bf(rel_h, "rel_h"), _bf(rel_w, "rel_w"), _i32(sigma, "sigma"), _bf(out, "out"),
+        C.c_int(groups), C.c_int(S), C.c_int(w), C.c_int(h), C.c_int(d), C.c_int(mask_block), C.c_double(r),
+        C.c_float(scale), _stream()))
+    return out
+
+
+# ------------------------------------------------------------------ routed MLP
+def ssam_score_tokens(x, scores=None, workspace=None):
+    B, gh, gw, D = x.shape
+    if scores is None:
+        scores = torch.empty((B, gh * gw), dtype=torch.float32, device=x.device)
+    need = lib().ssam_score_tokens_workspace_bytes(C.c_int(B), C.c_int(gh), C.c_int(gw))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check("ssam_score_tokens", lib().ssam_score_tokens(_bf(x, "x"), _f32(scores, "scores"), C.c_int(B), C.c_int(gh),
+                                                        C.c_int(gw), C.c_int(D), C.c_void_p(workspace.data_ptr()),
+                                                        C.c_size_t(workspace.numel()), _stream()))
+    return scores
+
+
+def ssam_select_tokens(scores, K, keep_idx=None):
+    B, N = scores.shape
+    if keep_idx is None:
+        keep_idx = torch.empty((B, K), dtype=torch.int32, device=scores.device)
+    _check("ssam_select_tokens", lib().ssam_select_tokens(_f32(scores, "scores"), _i32(keep_idx, "keep_idx"),
+                                                          C.c_int(B), C.c_int(N), C.c_int(K), _stream()))
+    return keep_idx
+
+
+def ssam_routed_mlp_workspace_bytes(B, K, D, Dm) -> int:
+    return lib().ssam_routed_mlp_workspace_bytes(C.c_int(B), C.c_int(K), C.c_int(D), C.c_int(Dm))
+
+
+def ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, workspace=None):
+    B, N, D = x.shape
+    Dm = w1.shape[0]
+    K = keep_idx.shape[1]
+    if workspace is None:
+        workspace = torch.empty(ssam_routed_mlp_workspace_bytes(B, K, D, Dm), dtype=torch.uint8, device=x.device)
+    _check("ssam_routed_mlp", lib().ssam_routed_mlp(
+        _bf(x, "x"), _i32(keep_idx, "keep_idx"), _f32(ln_g, "ln_g"), _f32(ln_b, "ln_b"), C.c_float(eps),
+        _bf(w1, "w1"), _f32(b1, "b1"), _bf(w2, "w2"), _f32(b2, "b2"),
+        C.c_int(B), C.c_int(N), C.c_int(D), C.c_int(Dm), C.c_int(K),
+        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return x
+
+
+# ------------------------------------------------------------------ block / encoder
+_BF16_FIELDS = ("wqkv", "rel_h", "rel_w", "wproj", "w1", "w2")
+
+
+def upload_block_weights(wdict: dict, device="cuda") -> dict:
+    """numpy fp32 dict (bf16-representable values) -> device tensors in the ABI's dtypes."""
+    out = {}
+    for k, v in wdict.items():
+        t = torch.from_numpy(np.ascontiguousarray(v))
+        out[k] = t.to(device=device, dtype=torch.bfloat16 if k in _BF16_FIELDS else torch.float32).contiguous()
+    return out
+
+
+def block_weights_struct(wt: dict) -> BlockWeights:
+    s = BlockWeights()
+    for name, _ in BlockWeights._fields_:
+        t = wt[name]
+        want = torch.bfloat16 if name in _BF16_FIELDS else torch.float32
+        _dev(t, want, name)
+        setattr(s, name, t.data_ptr())
+    return s
+
+
+def make_cfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps=1e-6) -> BlockCfg:
+    return BlockCfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps)
+
+
+def ssam_encoder_block_workspace_bytes(cfg: BlockCfg) -> int:
+    return lib().ssam_encoder_block_workspace_bytes(C.byref(cfg))
+
+
+def ssam_encoder_block(x, wstruct: BlockWeights, cfg: BlockCfg, gather_table, sigma, keep_idx, workspace=None):
+    if workspace is None:
+        workspace = torch.empty(ssam_encoder_block_workspace_bytes(cfg), dtype=torch.uint8, device=x.device)
+    _check("ssam_encoder_block", lib().ssam_encoder_block(
+        _bf(x, "x"), C.byref(wstruct), C.byref(cfg), _i32(gather_table, "gather_table"), _i32(sigma, "sigma"),
+        _i32(keep_idx, "keep_idx"), C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return x
+
+
+def ssam_encoder_workspace_bytes(cfg_local, cfg_global) -> int:
+    return lib().ssam_encoder_workspace_bytes(C.byref(cfg_local) if cfg_local is not None else None,
+                                              C.byref(cfg_global) if cfg_global is not None else None)
+
+
+def ssam_encoder_forward(x, wstructs, is_global, cfg_local, cfg_global, window_table, sigma_window,
+                         global_table, sigma_global, scores, keep_idx, workspace):
+    n = len(wstructs)
+    arr = (BlockWeights * n)(*wstructs)
+    flags = (C.c_uint8 * n)(*[1 if f else 0 for f in is_global])
+    _check("ssam_encoder_forward", lib().ssam_encoder_forward(
+        _bf(x, "x"), arr, flags, C.c_int(n),
+        C.byref(cfg_local) if cfg_local is not None else None,
+        C.byref(cfg_global) if cfg_global is not None else None,
+        _i32(window_table, "window_table"), _i32(sigma_window, "sigma_window"),
+        _i32(global_table, "global_table"), _i32(sigma_global, "sigma_global"),
+        _f32(scores, "scores"), _i32(keep_idx, "keep_idx"),
+        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return x

@@ -1,0 +1,154 @@
+// Composition of the structured-sparse encoder block: Stripe-Sort attention half
+// (Sec. 4.1, App. A.1) and Residual-Consistency MLP half (Sec. 4.2), and the
+// stack of blocks that shares one keep-set (Sec. 1, Sec. 4.1 "performed once").
+// Host code only: every step is a kernel of this library enqueued on the
+// caller's stream; intermediate tensors live in the caller's workspace.
+#include "gemm_kernel.h"
+
+int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
+                     int epilogue, const GemmRowMap &rm, int tile, hipStream_t st);
+
+namespace {
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct BlockGeom {
+    int S, w, nW, Nout, N, d;
+};
+
+bool block_geom(const ssam_block_cfg *c, BlockGeom &g)
+{
+    if (!c || c->B <= 0 || c->g <= 0 || c->D <= 0 || c->heads <= 0 || c->Dm <= 0 || c->ws < 0) return false;
+    if (c->D % c->heads != 0 || c->K <= 0 || c->K > c->g * c->g) return false;
+    g.N = c->g * c->g;
+    g.w = c->ws > 0 ? c->ws : c->g;
+    g.S = g.w * g.w;
+    int nws = (c->g + g.w - 1) / g.w;
+    g.nW = nws * nws;
+    g.Nout = g.nW * g.S;
+    g.d = c->D / c->heads;
+    return true;
+}
+
+size_t mlp_ws_bytes(int B, int K, int D, int Dm)
+{
+    return align256((size_t)B * K * D * 2) + align256((size_t)B * K * Dm * 2);
+}
+
+}  // namespace
+
+extern "C" size_t ssam_routed_mlp_workspace_bytes(int B, int K, int D, int Dm)
+{
+    if (B <= 0 || K <= 0 || D <= 0 || Dm <= 0) return 0;
+    return mlp_ws_bytes(B, K, D, Dm);
+}
+
+extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                               const void *w1, const float *b1, const void *w2, const float *b2,
+                               int B, int N, int D, int Dm, int K,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !keep_idx || !ln_g || !ln_b || !w1 || !b1 || !w2 || !b2 || !workspace) return SSAM_EINVAL;
+    if (B <= 0 || N <= 0 || D <= 0 || Dm <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
+    if (!ssam_aligned16(workspace)) return SSAM_EINVAL;
+    if (D % 128 != 0 || Dm % 128 != 0) return SSAM_EUNSUPPORTED;
+    if (workspace_bytes < mlp_ws_bytes(B, K, D, Dm)) return SSAM_EWORKSPACE;
+    unsigned char *ws = (unsigned char *)workspace;
+    void *a2 = ws;
+    void *hid = ws + align256((size_t)B * K * D * 2);
+    hipStream_t st = (hipStream_t)stream;
+    int rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
+    if (rc != SSAM_OK) return rc;
+    GemmRowMap none = { nullptr, 1, 0, 1 };
+    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, SSAM_EPI_BIAS_GELU, none, 0, st);
+    if (rc != SSAM_OK) return rc;
+    GemmRowMap scatter = { keep_idx, K, K, N };
+    return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0, st);
+}
+
+extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
+{
+    BlockGeom g;
+    if (!block_geom(cfg, g)) return 0;
+    size_t rows = (size_t)cfg->B * g.Nout;
+    size_t attn = align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2);
+    size_t mlp = mlp_ws_bytes(cfg->B, cfg->K, cfg->D, cfg->Dm);
+    return attn > mlp ? attn : mlp;
+}
+
+extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
+                                  const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    BlockGeom g;
+    if (!x || !w || !gather_table || !sigma || !keep_idx || !workspace || !block_geom(cfg, g)) return SSAM_EINVAL;
+    if (!(cfg->r > 0.0) || cfg->r > 1.0) return SSAM_EINVAL;
+    if (!ssam_aligned16(workspace) || !ssam_aligned16(x)) return SSAM_EINVAL;
+    if (cfg->D % 128 != 0 || cfg->Dm % 128 != 0) return SSAM_EUNSUPPORTED;
+    if (workspace_bytes < ssam_encoder_block_workspace_bytes(cfg)) return SSAM_EWORKSPACE;
+    const int B = cfg->B, D = cfg->D;
+    const int rows = B * g.Nout;
+    unsigned char *ws = (unsigned char *)workspace;
+    void *u = ws;                                             // LN1(x) in scan order; later the attention output
+    void *qkv = ws + align256((size_t)rows * D * 2);
+    hipStream_t st = (hipStream_t)stream;
+
+    int rc = ssam_ln_gather(x, gather_table, 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
+    if (rc != SSAM_OK) return rc;
+    GemmRowMap none = { nullptr, 1, 0, 1 };
+    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, SSAM_EPI_BIAS, none, 0, st);
+    if (rc != SSAM_OK) return rc;
+    const bf16 *qp = (const bf16 *)qkv;
+    rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, u,
+                               B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
+                               1.0f / sqrtf((float)g.d), stream);
+    if (rc != SSAM_OK) return rc;
+    GemmRowMap back = { gather_table, g.Nout, 0, g.N };
+    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, st);
+    if (rc != SSAM_OK) return rc;
+    return ssam_routed_mlp(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2,
+                           B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global)
+{
+    size_t a = cfg_local ? ssam_encoder_block_workspace_bytes(cfg_local) : 0;
+    size_t b = cfg_global ? ssam_encoder_block_workspace_bytes(cfg_global) : 0;
+    const ssam_block_cfg *c = cfg_local ? cfg_local : cfg_global;
+    size_t s = c ? align256(ssam_score_tokens_workspace_bytes(c->B, c->g, c->g)) : 0;
+    size_t m = a > b ? a : b;
+    return m > s ? m : s;
+}
+
+extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
+                                    const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,
+                                    const int32_t *window_table, const int32_t *sigma_window,
+                                    const int32_t *global_table, const int32_t *sigma_global,
+                                    float *scores, int32_t *keep_idx,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !weights || !is_global || n_blocks <= 0 || !scores || !keep_idx || !workspace) return SSAM_EINVAL;
+    bool any_local = false, any_global = false;
+    for (int i = 0; i < n_blocks; ++i) (is_global[i] ? any_global : any_local) = true;
+    if ((any_local && (!cfg_local || !window_table || !sigma_window)) ||
+        (any_global && (!cfg_global || !global_table || !sigma_global)))
+        return SSAM_EINVAL;
+    const ssam_block_cfg *c0 = any_local ? cfg_local : cfg_global;
+    if (any_local && any_global &&
+        (cfg_local->B != cfg_global->B || cfg_local->g != cfg_global->g || cfg_local->D != cfg_global->D ||
+         cfg_local->K != cfg_global->K))
+        return SSAM_EINVAL;
+    if (workspace_bytes < ssam_encoder_workspace_bytes(any_local ? cfg_local : nullptr, any_global ? cfg_global : nullptr))
+        return SSAM_EWORKSPACE;
+    int rc = ssam_score_tokens(x, scores, c0->B, c0->g, c0->g, c0->D, workspace, workspace_bytes, stream);
+    if (rc != SSAM_OK) return rc;
+    rc = ssam_select_tokens(scores, keep_idx, c0->B, c0->g * c0->g, c0->K, stream);
+    if (rc != SSAM_OK) return rc;
+    for (int i = 0; i < n_blocks; ++i) {
+        rc = is_global[i]
+                 ? ssam_encoder_block(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, stream)
+                 : ssam_encoder_block(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, stream);
+        if (rc != SSAM_OK) return rc;
+    }
+    return SSAM_OK;
+}

@@ -1,0 +1,191 @@
+// bf16 NT GEMM for gfx950: C = epilogue(A[M][K] * W[N][K]^T + bias), fp32
+// accumulation on the 32x32x16 bf16 MFMA.  Serves the block's qkv / proj / fc1 /
+// fc2 layers (the dense contractions of the SAM block; the routed MLP of
+// Sec. 4.2 reaches it with the gathered keep-set rows as A).
+//
+// Workgroup = 256 threads = 4 waves in a 2x2 grid over a BM x BN tile; each wave
+// owns (BM/2) x (BN/2) as 32x32 MFMA tiles.  K is consumed in slabs of 64:
+// global -> registers (prefetch of the next slab while the current one is
+// multiplied) -> LDS (double buffered, 16-byte chunks XOR-swizzled by row so
+// that the 8 lanes of a ds_read_b128 phase touch 8 different bank groups).
+// MFMA operand layout (32x32x16): lane l feeds row (l & 31), k-chunk (l >> 5)
+// of 8 consecutive bf16; the result register r of lane l is
+// C[8*(r/4) + 4*(l>>5) + (r&3)][l & 31] with rows from operand a, columns from b.
+// The epilogue stages 32-row slices of the fp32 result through LDS so that each
+// lane finishes 8 consecutive columns and issues 16-byte global accesses.
+#pragma once
+
+#include "common.h"
+
+struct GemmRowMap {
+    const int32_t *map;       // NULL unless the epilogue scatters
+    int rows_per_batch;
+    int map_batch_stride;
+    int dst_rows_per_batch;
+};
+
+constexpr int GEMM_BK = 64;
+constexpr int GEMM_THREADS = 256;
+
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes()
+{
+    size_t pipe = (size_t)2 * (BM + BN) * GEMM_BK * sizeof(bf16);
+    size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);
+    return pipe > epi ? pipe : epi;
+}
+
+// element offset of 16-byte chunk c (0..7) of row `row` in a [rows][64] bf16 slab
+__device__ __forceinline__ int gemm_swz(int row, int c) { return row * GEMM_BK + ((c ^ (row & 7)) << 3); }
+
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(GEMM_THREADS)
+gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
+                    bf16 *C, int M, int N, int K, int tiles_m, int tiles_n, GemmRowMap rm)
+{
+    constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
+    constexpr int A_LOADS = BM * 8 / GEMM_THREADS, B_LOADS = BN * 8 / GEMM_THREADS;
+    constexpr int GROUP_M = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16 *As = reinterpret_cast<bf16 *>(smem);                 // [2][BM*64]
+    bf16 *Bs = As + 2 * BM * GEMM_BK;                          // [2][BN*64]
+
+    // ---- tile assignment: workgroups are dealt round-robin to the 8 XCDs, so
+    // give each XCD a contiguous run of tiles (its own L2 then sees neighbouring
+    // A and W panels), ordered in bands of GROUP_M tile rows.
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (t >= total) return;
+    const int band = GROUP_M * tiles_n;
+    const int first_m = (t / band) * GROUP_M;
+    const int band_rows = min(GROUP_M, tiles_m - first_m);
+    const int tm = first_m + (t % band) % band_rows;
+    const int tn = (t % band) / band_rows;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    u32x4 ra[A_LOADS], rb[B_LOADS];
+    const int nk = K / GEMM_BK;
+
+#define GEMM_LOAD_GLOBAL(kt_)                                                                          \
+    {                                                                                                  \
+        const int k0_ = (kt_) * GEMM_BK;                                                               \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
+        {                                                                                              \
+            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
+            int m = min(m0 + row, M - 1); /* rows past M repeat the last row; never stored */         \
+            ra[i] = *reinterpret_cast<const u32x4 *>(A + (long)m * K + k0_ + c * 8);                   \
+        }                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                            \
+        {                                                                                              \
+            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
+            rb[i] = *reinterpret_cast<const u32x4 *>(W + (long)(n0 + row) * K + k0_ + c * 8);          \
+        }                                                                                              \
+    }
+#define GEMM_STORE_LDS(buf_)                                                                           \
+    {                                                                                                  \
+        bf16 *as_ = As + (buf_) * BM * GEMM_BK, *bs_ = Bs + (buf_) * BN * GEMM_BK;                     \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
+        {                                                                                              \
+            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
+            *reinterpret_cast<u32x4 *>(as_ + gemm_swz(row, c)) = ra[i];                                \
+        }                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                            \
+        {                                                                                              \
+            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
+            *reinterpret_cast<u32x4 *>(bs_ + gemm_swz(row, c)) = rb[i];                                \
+        }                                                                                              \
+    }
+
+    GEMM_LOAD_GLOBAL(0)
+    GEMM_STORE_LDS(0)
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) GEMM_LOAD_GLOBAL(kt + 1)
+        const bf16 *as = As + buf * BM * GEMM_BK, *bs = Bs + buf * BN * GEMM_BK;
+#pragma unroll
+        for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
+            bf16x8 af[MT], bfr[NT];
+            const int c = ks * 2 + half;
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                af[i] = *reinterpret_cast<const bf16x8 *>(as + gemm_swz(wm + i * 32 + l32, c));
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + gemm_swz(wn + j * 32 + l32, c));
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) GEMM_STORE_LDS(buf ^ 1)
+        __syncthreads();
+    }
+
+    // ---- epilogue: 32-row slices through a per-wave fp32 LDS region
+    constexpr int EPS = WN + 4;                 // floats per staged row (16-byte multiple, odd in 16-byte units)
+    constexpr int LPR = WN / 8;                 // lanes per row when each lane owns 8 columns
+    constexpr int RPP = 64 / LPR;               // rows per pass
+    float *stage = reinterpret_cast<float *>(smem) + wave * 32 * EPS;
+    const int cl = lane % LPR, rl = lane / LPR;
+    const int ncol = n0 + wn + cl * 8;
+    float bv[8];
+    {
+        const float4 *b4 = reinterpret_cast<const float4 *>(bias + ncol);
+        float4 x0 = b4[0], x1 = b4[1];
+        bv[0] = x0.x; bv[1] = x0.y; bv[2] = x0.z; bv[3] = x0.w;
+        bv[4] = x1.x; bv[5] = x1.y; bv[6] = x1.z; bv[7] = x1.w;
+    }
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                stage[(8 * (r >> 2) + 4 * half + (r & 3)) * EPS + j * 32 + l32] = acc[i][j][r];
+        __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+            const int row = pass * RPP + rl;
+            const int m = m0 + wm + i * 32 + row;
+            if (m >= M) continue;
+            const float4 *s4 = reinterpret_cast<const float4 *>(stage + row * EPS + cl * 8);
+            float4 y0 = s4[0], y1 = s4[1];
+            float v[8] = { y0.x + bv[0], y0.y + bv[1], y0.z + bv[2], y0.w + bv[3],
+                           y1.x + bv[4], y1.y + bv[5], y1.z + bv[6], y1.w + bv[7] };
+            if (EPI == SSAM_EPI_BIAS_GELU) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+            }
+            if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+                int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
+                int idx = rm.map[(long)b * rm.map_batch_stride + p];
+                if (idx < 0 || idx >= rm.dst_rows_per_batch) continue;
+                uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)b * rm.dst_rows_per_batch + idx) * N + ncol);
+                float o[8];
+                unpack_bf16x8(*dst, o);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += o[e];
+                *dst = pack_bf16x8(v);
+            } else {
+                *reinterpret_cast<uint4 *>(C + (long)m * N + ncol) = pack_bf16x8(v);
+            }
+        }
+    }
+}

@@ -1,0 +1,337 @@
+// HBM-bound kernels: row gather / scatter in scan order (Sec. 4.1), fused
+// LayerNorm + gather, token scores (Eq. 1) and keep-set selection (Sec. 4.2).
+// Every global access is a 16-byte vector per lane along the feature axis.
+#include "common.h"
+
+namespace {
+
+// ---------------------------------------------------------------- permute
+__global__ void __launch_bounds__(256)
+permute_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, uint4 *__restrict__ y,
+               int B, int Nin, int Nout, int chunks)
+{
+    long total = (long)B * Nout * chunks;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int c = (int)(i % chunks);
+        long row = i / chunks;
+        int p = (int)(row % Nout);
+        int b = (int)(row / Nout);
+        int src = idx[p];
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (src >= 0 && src < Nin) v = x[((long)b * Nin + src) * chunks + c];
+        y[i] = v;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+unpermute_kernel(const uint4 *__restrict__ y, const int32_t *__restrict__ idx, uint4 *x,
+                 const uint4 *residual, int B, int Nx, int Ny, int chunks)
+{
+    long total = (long)B * Ny * chunks;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int c = (int)(i % chunks);
+        long row = i / chunks;
+        int p = (int)(row % Ny);
+        int b = (int)(row / Ny);
+        int dst = idx[p];
+        if (dst < 0 || dst >= Nx) continue;
+        long o = ((long)b * Nx + dst) * chunks + c;
+        uint4 v = y[i];
+        if (residual) {
+            float a[8], r[8];
+            unpack_bf16x8(v, a);
+            unpack_bf16x8(residual[o], r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[e] += r[e];
+            v = pack_bf16x8(a);
+        }
+        x[o] = v;
+    }
+}
+
+// ---------------------------------------------------------------- LN + gather
+// One wave per output row; the row lives in registers (MAXC 16-byte chunks per
+// lane), two-pass statistics in fp32.
+template <int MAXC>
+__global__ void __launch_bounds__(256)
+ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, int idx_batch_stride,
+                 const float *__restrict__ gamma, const float *__restrict__ beta, float eps,
+                 uint4 *__restrict__ y, int B, int Nin, int Nout, int chunks)
+{
+    int lane = threadIdx.x & 63;
+    long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= (long)B * Nout) return;
+    int p = (int)(row % Nout), b = (int)(row / Nout);
+    int src = idx[(long)b * idx_batch_stride + p];
+    uint4 *yrow = y + row * chunks;
+    if (src < 0 || src >= Nin) {
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            int c = lane + 64 * i;
+            if (c < chunks) yrow[c] = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
+    const uint4 *xrow = x + ((long)b * Nin + src) * chunks;
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        int c = lane + 64 * i;
+        if (c < chunks) {
+            unpack_bf16x8(xrow[c], v[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[i][e];
+        }
+    }
+    int D = chunks * 8;
+    float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        int c = lane + 64 * i;
+        if (c < chunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { float t = v[i][e] - mean; q += t * t; }
+        }
+    }
+    float inv = rsqrtf(wave_sum(q) / (float)D + eps);
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        int c = lane + 64 * i;
+        if (c < chunks) {
+            const float4 *g4 = reinterpret_cast<const float4 *>(gamma) + 2 * c;
+            const float4 *b4 = reinterpret_cast<const float4 *>(beta) + 2 * c;
+            float4 g0 = g4[0], g1 = g4[1], b0 = b4[0], b1 = b4[1];
+            float gg[8] = { g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w };
+            float bb[8] = { b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w };
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * inv * gg[e] + bb[e];
+            yrow[c] = pack_bf16x8(o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- scores
+// channel sum of every token: one wave per token
+__global__ void __launch_bounds__(256)
+channel_sum_kernel(const uint4 *__restrict__ x, float *__restrict__ csum, long tokens, int chunks)
+{
+    int lane = threadIdx.x & 63;
+    long t = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (t >= tokens) return;
+    const uint4 *row = x + t * chunks;
+    float s = 0.f;
+    for (int c = lane; c < chunks; c += 64) {
+        float f[8];
+        unpack_bf16x8(row[c], f);
+        s += ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+    }
+    s = wave_sum(s);
+    if (lane == 0) csum[t] = s;
+}
+
+// Sobel magnitude with zero padding on the channel-sum map
+__global__ void __launch_bounds__(256)
+sobel_kernel(const float *__restrict__ csum, float *__restrict__ scores, int B, int gh, int gw)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long n = (long)gh * gw;
+    if (i >= (long)B * n) return;
+    int b = (int)(i / n), cell = (int)(i % n), row = cell / gw, col = cell % gw;
+    const float *c = csum + (long)b * n;
+    auto at = [&](int rr, int cc) -> float {
+        return (rr < 0 || rr >= gh || cc < 0 || cc >= gw) ? 0.f : c[rr * gw + cc];
+    };
+    float a00 = at(row - 1, col - 1), a01 = at(row - 1, col), a02 = at(row - 1, col + 1);
+    float a10 = at(row, col - 1), a12 = at(row, col + 1);
+    float a20 = at(row + 1, col - 1), a21 = at(row + 1, col), a22 = at(row + 1, col + 1);
+    float gx = (a02 - a00) + 2.f * (a12 - a10) + (a22 - a20);
+    float gy = (a20 - a00) + 2.f * (a21 - a01) + (a22 - a02);
+    scores[i] = sqrtf(gx * gx + gy * gy);
+}
+
+// ---------------------------------------------------------------- select
+// Order-preserving key: larger float <=> larger unsigned.  NaN -> -inf, -0 -> +0.
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t u = __float_as_uint(s);
+    if ((u & 0x7fffffffu) > 0x7f800000u) u = 0xff800000u;   // NaN ranks as -inf
+    if (u == 0x80000000u) u = 0u;                            // -0.0 == +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int SEL_THREADS = 1024;
+
+// exclusive prefix sum of one flag per thread over the block; returns the
+// thread's offset and (through total) the block total.  scratch: 16 ints.
+__device__ __forceinline__ int block_exclusive_count(bool flag, int *scratch, int &total)
+{
+    int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long ballot = __ballot(flag);
+    int before = __popcll(ballot & ((1ull << lane) - 1ull));
+    if (lane == 0) scratch[wave] = __popcll(ballot);
+    __syncthreads();
+    int base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < SEL_THREADS / 64; ++w) {
+        int c = scratch[w];
+        if (w < wave) base += c;
+        sum += c;
+    }
+    __syncthreads();
+    total = sum;
+    return base + before;
+}
+
+// One workgroup per image: 4 passes of an 8-bit radix select find the key of
+// the K-th largest score, then one ordered compaction pass writes every index
+// with a larger key plus the lowest-index ties, in ascending index order.
+__global__ void __launch_bounds__(SEL_THREADS)
+select_kernel(const float *__restrict__ scores, int32_t *__restrict__ keep, int N, int K)
+{
+    __shared__ int hist[256];
+    __shared__ int scratch[SEL_THREADS / 64];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+    const float *s = scores + (long)blockIdx.x * N;
+    int32_t *out = keep + (long)blockIdx.x * K;
+
+    uint32_t prefix = 0, prefix_mask = 0;
+    int remaining = K;   // how many of the keys matching the prefix are still to be taken
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = threadIdx.x; i < 256; i += SEL_THREADS) hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < N; i += SEL_THREADS) {
+            uint32_t key = score_key(s[i]);
+            if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int rem = remaining, bucket = 255;
+            for (; bucket > 0; --bucket) {
+                int c = hist[bucket];
+                if (c >= rem) break;
+                rem -= c;
+            }
+            sh_prefix = prefix | ((uint32_t)bucket << shift);
+            sh_remaining = rem;
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        remaining = sh_remaining;
+        prefix_mask |= 255u << shift;
+        __syncthreads();
+    }
+    // prefix = key of the K-th largest element; `remaining` ties are taken, lowest index first
+    const uint32_t threshold = prefix;
+    int taken = 0, ties_seen = 0;
+    for (int base = 0; base < N; base += SEL_THREADS) {
+        int i = base + threadIdx.x;
+        uint32_t key = (i < N) ? score_key(s[i]) : 0u;
+        bool gt = (i < N) && key > threshold;
+        bool eq = (i < N) && key == threshold;
+        int eq_total, sel_total;
+        int eq_rank = ties_seen + block_exclusive_count(eq, scratch, eq_total);
+        bool sel = gt || (eq && eq_rank < remaining);
+        int pos = taken + block_exclusive_count(sel, scratch, sel_total);
+        if (sel && pos < K) out[pos] = i;
+        ties_seen += eq_total;
+        taken += sel_total;
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- entry points
+static bool movers_args_ok(const void *a, const void *b, const void *c, int B, int n1, int n2, int D)
+{
+    return a && b && c && ssam_aligned16(a) && ssam_aligned16(c) && B > 0 && n1 > 0 && n2 > 0 && D > 0 && D % 8 == 0;
+}
+
+static int mover_grid(long total_chunks)
+{
+    long blocks = (total_chunks + 255) / 256;
+    return (int)(blocks < 1 ? 1 : (blocks > 256L * 32 ? 256L * 32 : blocks));
+}
+
+extern "C" int ssam_permute(const void *x, const int32_t *idx, void *y, int B, int Nin, int Nout, int D, void *stream)
+{
+    if (!movers_args_ok(x, idx, y, B, Nin, Nout, D)) return SSAM_EINVAL;
+    int chunks = D / 8;
+    hipLaunchKernelGGL(permute_kernel, dim3(mover_grid((long)B * Nout * chunks)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)x, idx, (uint4 *)y, B, Nin, Nout, chunks);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_unpermute(const void *y, const int32_t *idx, void *x, const void *residual,
+                              int B, int Nx, int Ny, int D, void *stream)
+{
+    if (!movers_args_ok(y, idx, x, B, Nx, Ny, D)) return SSAM_EINVAL;
+    if (residual && !ssam_aligned16(residual)) return SSAM_EINVAL;
+    int chunks = D / 8;
+    hipLaunchKernelGGL(unpermute_kernel, dim3(mover_grid((long)B * Ny * chunks)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)y, idx, (uint4 *)x, (const uint4 *)residual, B, Nx, Ny, chunks);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_ln_gather(const void *x, const int32_t *idx, int idx_batch_stride,
+                              const float *gamma, const float *beta, float eps, void *y,
+                              int B, int Nin, int Nout, int D, void *stream)
+{
+    if (!movers_args_ok(x, idx, y, B, Nin, Nout, D) || !gamma || !beta || idx_batch_stride < 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(gamma) || !ssam_aligned16(beta)) return SSAM_EINVAL;
+    if (D > 2048) return SSAM_EUNSUPPORTED;
+    int chunks = D / 8;
+    long rows = (long)B * Nout;
+    dim3 grid(ssam_div_up(rows, 4)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (chunks <= 128)
+        hipLaunchKernelGGL(ln_gather_kernel<2>, grid, block, 0, st, (const uint4 *)x, idx, idx_batch_stride,
+                           gamma, beta, eps, (uint4 *)y, B, Nin, Nout, chunks);
+    else if (chunks <= 192)
+        hipLaunchKernelGGL(ln_gather_kernel<3>, grid, block, 0, st, (const uint4 *)x, idx, idx_batch_stride,
+                           gamma, beta, eps, (uint4 *)y, B, Nin, Nout, chunks);
+    else
+        hipLaunchKernelGGL(ln_gather_kernel<4>, grid, block, 0, st, (const uint4 *)x, idx, idx_batch_stride,
+                           gamma, beta, eps, (uint4 *)y, B, Nin, Nout, chunks);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" size_t ssam_score_tokens_workspace_bytes(int B, int gh, int gw)
+{
+    if (B <= 0 || gh <= 0 || gw <= 0) return 0;
+    return (size_t)B * gh * gw * sizeof(float);
+}
+
+extern "C" int ssam_score_tokens(const void *x, float *scores, int B, int gh, int gw, int D,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !scores || !workspace || B <= 0 || gh <= 0 || gw <= 0 || D <= 0 || D % 8 != 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(x) || !ssam_aligned16(workspace)) return SSAM_EINVAL;
+    if (workspace_bytes < ssam_score_tokens_workspace_bytes(B, gh, gw)) return SSAM_EWORKSPACE;
+    long tokens = (long)B * gh * gw;
+    float *csum = (float *)workspace;
+    hipLaunchKernelGGL(channel_sum_kernel, dim3(ssam_div_up(tokens, 4)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)x, csum, tokens, D / 8);
+    SSAM_CHECK_LAUNCH();
+    hipLaunchKernelGGL(sobel_kernel, dim3(ssam_div_up(tokens, 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const float *)csum, scores, B, gh, gw);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_select_tokens(const float *scores, int32_t *keep_idx, int B, int N, int K, void *stream)
+{
+    if (!scores || !keep_idx || B <= 0 || N <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
+    if (N > 65536) return SSAM_EUNSUPPORTED;
+    hipLaunchKernelGGL(select_kernel, dim3(B), dim3(SEL_THREADS), 0, (hipStream_t)stream, scores, keep_idx, N, K);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}

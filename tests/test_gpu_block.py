@@ -1,0 +1,229 @@
+"""GPU parity of Stripe-Sort attention, the routed MLP, the encoder block and the
+block stack against the CPU oracle, element by element on the same seeded
+inputs.  Floating-point bar: max relative error 2e-2 (bf16 compute, fp32
+accumulate); integer outputs (keep-set) bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import announce, assert_close, to_np
+from paper_2605_17633_amd import binding as B
+from paper_2605_17633_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(DEV).to(torch.bfloat16).contiguous()
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(DEV)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(DEV)
+
+
+# ------------------------------------------------------------------ attention
+def run_attention_case(groups, w, h, d, Bm, r, G=4, qk_scale=0.7, rel_scale=0.02, seed=0):
+    rng = np.random.default_rng(seed)
+    S = w * w
+    qkv_sp = inputs.qkv_tensors(rng, groups, S, h, d, scale=1.0)          # spatial order [g,S,3,h,d]
+    qkv_sp[:, :, :2] = inputs.bf16_round(qkv_sp[:, :, :2] * qk_scale)
+    rel_h = inputs.bf16_round(rng.normal(0, rel_scale, size=(2 * w - 1, d)).astype(np.float32))
+    rel_w = inputs.bf16_round(rng.normal(0, rel_scale, size=(2 * w - 1, d)).astype(np.float32))
+    sigma, _ = oracle.grid_sigma(w, G)
+    qkv_scan = np.ascontiguousarray(qkv_sp[:, sigma])                       # tokens in scan order for the GPU
+    out = B.ssam_sparse_attention(dev_bf16(qkv_scan), dev_bf16(rel_h), dev_bf16(rel_w), dev_i32(sigma), w, Bm, r)
+    got = to_np(out).reshape(groups, S, h, d)
+    ref = np.empty((groups, S, h, d), np.float32)
+    for g in range(groups):
+        q, k, v = (np.ascontiguousarray(qkv_sp[g, :, i].transpose(1, 0, 2)) for i in range(3))   # [h,S,d]
+        o = oracle.attention(q, k, v, rel_h, rel_w, w, G, Bm, r)                                 # spatial [h,S,d]
+        ref[g] = o.transpose(1, 0, 2)[sigma]                                                       # -> scan order
+    return got, ref
+
+
+@pytest.mark.parametrize("w,h,d,Bm,r", [
+    (14, 2, 64, 32, 0.4), (14, 2, 80, 32, 0.4), (14, 1, 80, 32, 1.0), (14, 1, 64, 32, 0.2), (14, 1, 80, 32, 0.6),
+    (8, 2, 32, 32, 0.5), (6, 1, 16, 32, 0.5), (4, 1, 64, 32, 1.0),
+])
+def test_window_attention(w, h, d, Bm, r):
+    announce("window attention", w, h, d, Bm, r)
+    got, ref = run_attention_case(3, w, h, d, Bm, r)
+    assert_close(got, ref, f"attention w={w} d={d} r={r}")
+
+
+@pytest.mark.parametrize("w,h,d,r", [
+    (16, 2, 64, 0.5), (16, 1, 80, 1.0), (28, 1, 80, 0.4), (28, 2, 64, 0.3), (12, 1, 32, 0.5), (64, 1, 80, 0.4), (64, 1, 64, 0.3),
+])
+def test_global_attention(w, h, d, r):
+    announce("global attention", w, h, d, r)
+    got, ref = run_attention_case(2 if w < 64 else 1, w, h, d, 128, r)
+    assert_close(got, ref, f"global attention w={w} d={d} r={r}")
+
+
+@pytest.mark.parametrize("w,d,Bm,r", [(14, 80, 32, 0.4), (14, 64, 32, 0.3), (32, 80, 128, 0.4)])
+def test_attention_stress_peaky_softmax(w, d, Bm, r):
+    """q, k with std 2 (logits std ~4) and bias std ~1: mask or bias mistakes cannot hide behind a flat softmax."""
+    announce("stress attention", w, d, Bm, r)
+    got, ref = run_attention_case(2, w, 2, d, Bm, r, qk_scale=2.0, rel_scale=0.5 / np.sqrt(d), seed=9)
+    assert_close(got, ref, f"stress attention w={w} d={d}")
+
+
+def test_attention_plain_morton_order():
+    announce("attention G=1")
+    got, ref = run_attention_case(2, 14, 2, 64, 32, 0.4, G=1)
+    assert_close(got, ref, "attention G=1")
+
+
+def test_attention_rejects_unsupported():
+    qkv = torch.zeros((1, 196, 3, 1, 48), dtype=torch.bfloat16, device=DEV)
+    rel = torch.zeros((27, 48), dtype=torch.bfloat16, device=DEV)
+    sig = torch.zeros(196, dtype=torch.int32, device=DEV)
+    with pytest.raises(B.SsamError) as e:
+        B.ssam_sparse_attention(qkv, rel, rel, sig, 14, 32, 0.4)
+    assert e.value.code == B.EUNSUPPORTED
+    qkv = torch.zeros((1, 196, 3, 1, 64), dtype=torch.bfloat16, device=DEV)
+    rel = torch.zeros((27, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.SsamError) as e:
+        B.ssam_sparse_attention(qkv, rel, rel, sig, 14, 64, 0.4)       # mask tile the kernels are not built for
+    assert e.value.code == B.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ routed MLP
+@pytest.mark.parametrize("B_,n,D,Dm,rho", [(2, 784, 768, 3072, 0.4), (1, 500, 128, 256, 0.3), (1, 300, 1280, 5120, 1.0)])
+def test_routed_mlp(B_, n, D, Dm, rho):
+    announce("routed_mlp", B_, n, D, Dm, rho)
+    rng = np.random.default_rng(20)
+    wt = inputs.block_weights(rng, D, D // 64, Dm, 14)
+    x = inputs.bf16_round(rng.normal(size=(B_, n, D)).astype(np.float32))
+    K = oracle.keep_count(n, rho)
+    scores = inputs.lognormal_scores(rng, B_, n)
+    keep = np.stack([oracle.select_tokens(scores[b], K) for b in range(B_)])
+    wd = B.upload_block_weights(wt)
+    xd = dev_bf16(x)
+    B.ssam_routed_mlp(xd, dev_i32(keep), wd["ln2_g"], wd["ln2_b"], 1e-6, wd["w1"], wd["b1"], wd["w2"], wd["b2"])
+    got = to_np(xd)
+    for b in range(B_):
+        ref = oracle.routed_mlp(x[b], keep[b], wt["ln2_g"], wt["ln2_b"], wt["w1"], wt["b1"], wt["w2"], wt["b2"])
+        rest = np.setdiff1d(np.arange(n), keep[b])
+        assert np.array_equal(got[b][rest].view(np.uint32), x[b][rest].view(np.uint32))     # bypass rows bit-identical
+        # the update itself (y - x) carries the result; x + delta would hide errors behind the residual
+        assert_close(got[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"mlp delta b={b}")
+
+
+# ------------------------------------------------------------------ encoder block
+def make_block_case(seed, B_, g, shape, ws, rho, scale_w=1.0):
+    rng = np.random.default_rng(seed)
+    w = ws if ws > 0 else g
+    wt = inputs.block_weights(rng, shape.D, shape.heads, shape.Dm, w)
+    if scale_w != 1.0:
+        for kname in ("wqkv", "wproj", "w1", "w2", "rel_h", "rel_w"):
+            wt[kname] = inputs.bf16_round(wt[kname] * scale_w)
+    x = inputs.token_field(rng, B_, g, shape.D)
+    n = g * g
+    K = oracle.keep_count(n, rho)
+    keep = np.stack([oracle.select_tokens(oracle.score_tokens(x[b]), K) for b in range(B_)])
+    return wt, x, keep, K
+
+
+def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4):
+    B_, g = x.shape[0], x.shape[1]
+    n = g * g
+    wd = B.upload_block_weights(wt)
+    cfg = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, ws, Bm, keep.shape[1], r)
+    if ws > 0:
+        table = dev_i32(oracle.window_table(g, ws, G))
+        sigma = dev_i32(oracle.grid_sigma(ws, G)[0])
+    else:
+        table = dev_i32(oracle.grid_sigma(g, G)[0])
+        sigma = table
+    xd = dev_bf16(x.reshape(B_, n, shape.D))
+    B.ssam_encoder_block(xd, B.block_weights_struct(wd), cfg, table, sigma, dev_i32(keep))
+    torch.cuda.synchronize()
+    return to_np(xd).reshape(x.shape), wd
+
+
+@pytest.mark.parametrize("name,g,ws,Bm,r,rho,scale_w", [
+    ("config0 windowed ViT-B 28x28", 28, 14, 32, 0.4, 0.4, 1.0),
+    ("config0 dense limit", 28, 14, 32, 1.0, 1.0, 1.0),
+    ("global 28x28", 28, 0, 128, 0.4, 0.4, 1.0),
+    ("padded windows 20x20", 20, 14, 32, 0.4, 0.3, 1.0),
+    ("large weights windowed", 28, 14, 32, 0.4, 0.4, 4.0),
+])
+def test_encoder_block_vit_b(name, g, ws, Bm, r, rho, scale_w):
+    announce("encoder_block", name)
+    shape = inputs.VIT_B
+    wt, x, keep, K = make_block_case(30, 2, g, shape, ws, rho, scale_w)
+    got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, r)
+    ow = oracle.BlockWeights(**wt)
+    for b in range(x.shape[0]):
+        ref = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, r, keep[b])
+        assert_close(got[b] - x[b], ref - x[b], f"{name}: block delta b={b}")
+        attn_only = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, r, np.zeros(0, np.int32))
+        rest = np.setdiff1d(np.arange(g * g), keep[b])
+        assert_close(got[b].reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest],
+                     attn_only.reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest], f"{name}: attention-only rows b={b}")
+
+
+def test_encoder_block_vit_h_dims():
+    """One windowed and one global block at ViT-H width (d = 80) on a 28x28 grid."""
+    shape = inputs.VIT_H
+    for ws, Bm in ((14, 32), (0, 128)):
+        announce("encoder_block ViT-H dims", ws)
+        wt, x, keep, K = make_block_case(31, 1, 28, shape, ws, 0.4)
+        got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4)
+        ref = oracle.encoder_block(x[0], oracle.BlockWeights(**wt), shape.heads, ws, 4, Bm, 0.4, keep[0])
+        assert_close(got[0] - x[0], ref - x[0], f"ViT-H block ws={ws}")
+
+
+# ------------------------------------------------------------------ block stack
+def test_encoder_forward_small_stack():
+    """3 blocks (the last one global) at ViT-B width on a 28x28 grid: scores, keep-set and
+    every block through ssam_encoder_forward, against the oracle's encoder."""
+    announce("encoder_forward small stack")
+    shape = inputs.ModelShape("vit_b_3", 768, 3, 12, 3072, (2,), 14)
+    g, B_, r, rho = 28, 2, 0.4, 0.4
+    n = g * g
+    wts = inputs.encoder_weights(40, shape, g)
+    rng = np.random.default_rng(41)
+    x = inputs.token_field(rng, B_, g, shape.D)
+    K = oracle.keep_count(n, rho)
+    wds = [B.upload_block_weights(w) for w in wts]
+    structs = [B.block_weights_struct(w) for w in wds]
+    flags = [i in shape.global_blocks for i in range(shape.depth)]
+    cfg_l = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r)
+    cfg_g = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, 0, 128, K, r)
+    wtab, wsig = dev_i32(oracle.window_table(g, shape.ws, 4)), dev_i32(oracle.grid_sigma(shape.ws, 4)[0])
+    gtab = dev_i32(oracle.grid_sigma(g, 4)[0])
+    xd = dev_bf16(x.reshape(B_, n, shape.D))
+    scores = torch.empty((B_, n), dtype=torch.float32, device=DEV)
+    keep = torch.empty((B_, K), dtype=torch.int32, device=DEV)
+    ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cfg_l, cfg_g), dtype=torch.uint8, device=DEV)
+    B.ssam_encoder_forward(xd, structs, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf)
+    torch.cuda.synchronize()
+    got = to_np(xd).reshape(x.shape)
+    keep_gpu = keep.cpu().numpy()
+    for b in range(B_):
+        ref, keep_ref = oracle.encoder(x[b], [oracle.BlockWeights(**w) for w in wts], shape.heads, shape.ws,
+                                       shape.global_blocks, 4, r, rho)
+        sc_ref = oracle.score_tokens(x[b]).reshape(-1)
+        np.testing.assert_allclose(to_np(scores[b]), sc_ref, rtol=2e-5, atol=2e-5 * sc_ref.max())
+        # the keep-set is an integer decision on fp32 scores: identical unless two scores at the
+        # threshold are closer than the fp32 summation noise; what is unique must match
+        diff = np.setxor1d(keep_gpu[b], keep_ref)
+        thr = np.sort(sc_ref)[::-1][K - 1]
+        assert np.all(np.abs(sc_ref[diff] - thr) <= 1e-4 * thr), "keep-sets differ away from the threshold"
+        if diff.size == 0:
+            assert_close(got[b] - x[b], ref - x[b], f"encoder stack b={b}")
+        else:                                                      # rerun the oracle on the GPU's (valid) keep-set
+            y = x[b]
+            for i, w in enumerate(wts):
+                glob = i in shape.global_blocks
+                y = oracle.encoder_block(y, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
+                                         128 if glob else 32, r, keep_gpu[b])
+            assert_close(got[b] - x[b], y - x[b], f"encoder stack b={b} (threshold tie)")

@@ -1,0 +1,180 @@
+"""GPU parity of the individual entry points against the CPU oracle (or, for the
+pure data movers and the dense contraction, against the definition written with
+numpy on the oracle's tables).  Every call goes through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import announce, assert_close, to_np
+from paper_2605_17633_amd import binding as B
+from paper_2605_17633_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(DEV).to(torch.bfloat16).contiguous()
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(DEV)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(DEV)
+
+
+# ------------------------------------------------------------------ integer layer
+@pytest.mark.parametrize("gh,gw,G", [(14, 14, 4), (28, 28, 4), (64, 64, 4), (70, 70, 4), (5, 9, 1), (14, 14, 1), (128, 128, 4)])
+def test_perm_device_bit_exact(gh, gw, G):
+    announce("perm_device", gh, gw, G)
+    perm, inv = B.ssam_build_perm_device(gh, gw, G)
+    torch.cuda.synchronize()
+    sigma, sinv = oracle.stripe_sort(oracle.morton_order(gh, gw), G)
+    assert np.array_equal(perm.cpu().numpy(), sigma)
+    assert np.array_equal(inv.cpu().numpy(), sinv)
+
+
+# ------------------------------------------------------------------ movers
+@pytest.mark.parametrize("B_,g,ws,D", [(2, 28, 14, 768), (1, 64, 14, 1280), (3, 16, 6, 64)])
+def test_permute_unpermute_roundtrip(B_, g, ws, D):
+    announce("permute", B_, g, ws, D)
+    rng = np.random.default_rng(0)
+    x = inputs.bf16_round(rng.normal(size=(B_, g * g, D)).astype(np.float32))
+    table = oracle.window_table(g, ws, 4)
+    xd, td = dev_bf16(x), dev_i32(table)
+    y = B.ssam_permute(xd, td)
+    expect = np.where(table[None, :, None] >= 0, x[:, np.maximum(table, 0)], 0.0)
+    assert np.array_equal(to_np(y), expect)                       # pure copy: bit exact
+    back = torch.full_like(xd, 7.0)
+    B.ssam_unpermute(y, td, back)
+    assert np.array_equal(to_np(back), x)                          # inverse restores the input bit for bit
+    res = inputs.bf16_round(rng.normal(size=x.shape).astype(np.float32))
+    out = torch.zeros_like(xd)
+    B.ssam_unpermute(y, td, out, dev_bf16(res))
+    assert np.array_equal(to_np(out), inputs.bf16_round(x + res))  # one fp32 add, one rounding
+    # global order
+    sigma, sinv = oracle.grid_sigma(g, 4)
+    y2 = B.ssam_permute(xd, dev_i32(sigma))
+    assert np.array_equal(to_np(y2), x[:, sigma])
+    assert np.array_equal(to_np(B.ssam_permute(y2, dev_i32(sinv))), x)
+
+
+@pytest.mark.parametrize("B_,n,D,K", [(2, 784, 768, 313), (1, 300, 1280, 300), (2, 100, 1024, 7), (1, 50, 2048, 50), (1, 64, 64, 64)])
+def test_ln_gather(B_, n, D, K):
+    announce("ln_gather", B_, n, D, K)
+    rng = np.random.default_rng(1)
+    x = inputs.bf16_round((rng.normal(size=(B_, n, D)) * 2 + 0.5).astype(np.float32))
+    g = (1 + 0.1 * rng.normal(size=D)).astype(np.float32)
+    b = (0.1 * rng.normal(size=D)).astype(np.float32)
+    idx = np.stack([rng.permutation(n)[:K] for _ in range(B_)]).astype(np.int32)
+    idx[:, 0] = -1                                                 # a padding slot
+    y = B.ssam_ln_gather(dev_bf16(x), dev_i32(idx), K, dev_f32(g), dev_f32(b), 1e-6, K)
+    xd = torch.from_numpy(x).double()
+    ref = torch.nn.functional.layer_norm(xd, (D,), torch.from_numpy(g).double(), torch.from_numpy(b).double(), 1e-6).numpy()
+    ref = np.stack([ref[i, np.maximum(idx[i], 0)] for i in range(B_)])
+    ref[:, 0] = 0.0
+    assert_close(to_np(y), ref, "ln_gather", tol=1e-2)
+    assert np.all(to_np(y)[:, 0] == 0.0)
+
+
+# ------------------------------------------------------------------ scores / select
+@pytest.mark.parametrize("B_,g,D", [(2, 28, 768), (1, 64, 1280), (3, 9, 64)])
+def test_score_tokens(B_, g, D):
+    announce("score_tokens", B_, g, D)
+    rng = np.random.default_rng(2)
+    x = inputs.token_field(rng, B_, g, D)
+    s = to_np(B.ssam_score_tokens(dev_bf16(x)))
+    ref = np.stack([oracle.score_tokens(x[b]).reshape(-1) for b in range(B_)])
+    np.testing.assert_allclose(s, ref, rtol=2e-5, atol=2e-5 * np.abs(ref).max())
+
+
+def _check_select(scores, K):
+    B_, n = scores.shape
+    got = B.ssam_select_tokens(dev_f32(scores), K).cpu().numpy()
+    for b in range(B_):
+        assert np.array_equal(got[b], oracle.select_tokens(scores[b], K)), (b, n, K)
+
+
+@pytest.mark.parametrize("n,rho", [(4096, 0.4), (4096, 0.3), (4096, 0.2), (4096, 0.6), (4096, 1.0), (784, 0.4), (100, 0.01), (5000, 0.5)])
+def test_select_tokens_lognormal(n, rho):
+    announce("select", n, rho)
+    rng = np.random.default_rng(3)
+    _check_select(inputs.lognormal_scores(rng, 4, n), oracle.keep_count(n, rho))
+
+
+def test_select_tokens_ties_and_specials():
+    announce("select ties")
+    rng = np.random.default_rng(4)
+    n = 4096
+    s = inputs.lognormal_scores(rng, 5, n)
+    s[0] = 1.0                                                      # all equal -> 0..K-1
+    s[1] = np.round(s[1] * 2) / 2                                   # heavy ties at the threshold
+    s[2, ::3] = 0.0
+    s[2, 1::3] = -0.0
+    s[2, 2::3] = -1.0                                               # signed zeros tie, negatives rank below
+    s[3] = -s[3]                                                    # all negative
+    s[4, :100] = np.nan
+    s[4, 100:200] = -np.inf
+    s[4, 200:300] = np.inf
+    for K in (1, 37, 1638, 2800, 4096):
+        _check_select(s, K)
+
+
+# ------------------------------------------------------------------ dense contraction
+def _gemm_ref(A, W, b):
+    return A.astype(np.float64) @ W.astype(np.float64).T + b.astype(np.float64)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("M,N,K", [(300, 256, 64), (1000, 512, 192), (513, 768, 768), (64, 256, 128)])
+def test_linear_bias_and_gelu(tile, M, N, K):
+    announce("linear", tile, M, N, K)
+    rng = np.random.default_rng(5)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    ref = _gemm_ref(A, W, b)
+    out = B.ssam_linear(dev_bf16(A), dev_bf16(W), dev_f32(b), tile=tile)
+    assert_close(to_np(out), ref, f"linear bias tile{tile}", tol=1e-2)
+    out = B.ssam_linear(dev_bf16(A), dev_bf16(W), dev_f32(b), epilogue=B.EPI_BIAS_GELU, tile=tile)
+    gelu = torch.nn.functional.gelu(torch.from_numpy(ref)).numpy()
+    assert_close(to_np(out), gelu, f"linear gelu tile{tile}", tol=1e-2)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+def test_linear_scatter_add(tile):
+    announce("linear scatter", tile)
+    rng = np.random.default_rng(6)
+    B_, n, Kk, N, K = 2, 500, 210, 256, 128
+    A = inputs.bf16_round(rng.normal(size=(B_ * Kk, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    x = inputs.bf16_round(rng.normal(size=(B_, n, N)).astype(np.float32))
+    idx = np.stack([np.sort(rng.permutation(n)[:Kk]) for _ in range(B_)]).astype(np.int32)
+    idx[1, 5] = -1
+    xd = dev_bf16(x)
+    B.ssam_linear(dev_bf16(A), dev_bf16(W), dev_f32(b), xd, epilogue=B.EPI_BIAS_SCATTER_ADD, row_map=dev_i32(idx),
+                  rows_per_batch=Kk, map_batch_stride=Kk, dst_rows_per_batch=n, tile=tile)
+    got = to_np(xd)
+    prod = _gemm_ref(A, W, b).reshape(B_, Kk, N)
+    ref = x.astype(np.float64).copy()
+    touched = np.zeros((B_, n), bool)
+    for bi in range(B_):
+        for j in range(Kk):
+            if idx[bi, j] >= 0:
+                ref[bi, idx[bi, j]] += prod[bi, j]
+                touched[bi, idx[bi, j]] = True
+    assert np.array_equal(got[~touched].view(np.uint32), x[~touched].view(np.uint32))   # untouched rows bit-identical
+    assert_close(got[touched] - x[touched], ref[touched] - x[touched], f"scatter-add delta tile{tile}")
+
+
+def test_linear_rejects_unsupported():
+    A = torch.zeros((8, 48), dtype=torch.bfloat16, device=DEV)
+    W = torch.zeros((128, 48), dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros(128, device=DEV)
+    with pytest.raises(B.SsamError) as e:
+        B.ssam_linear(A, W, b)
+    assert e.value.code == B.EUNSUPPORTED
