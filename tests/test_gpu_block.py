@@ -100,6 +100,8 @@ def test_routed_mlp(B_, n, D, Dm, rho):
     announce("routed_mlp", B_, n, D, Dm, rho)
     rng = np.random.default_rng(20)
     wt = inputs.block_weights(rng, D, D // 64, Dm, 14)
+    for kname in ("w1", "w2"):                                      # make the update comparable to x
+        wt[kname] = inputs.bf16_round(wt[kname] * 4)
     x = inputs.bf16_round(rng.normal(size=(B_, n, D)).astype(np.float32))
     K = oracle.keep_count(n, rho)
     scores = inputs.lognormal_scores(rng, B_, n)
@@ -113,7 +115,8 @@ def test_routed_mlp(B_, n, D, Dm, rho):
         rest = np.setdiff1d(np.arange(n), keep[b])
         assert np.array_equal(got[b][rest].view(np.uint32), x[b][rest].view(np.uint32))     # bypass rows bit-identical
         # the update itself (y - x) carries the result; x + delta would hide errors behind the residual
-        assert_close(got[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"mlp delta b={b}")
+        assert_close(got[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"mlp delta b={b}",
+                     stored=ref[keep[b]])
 
 
 # ------------------------------------------------------------------ encoder block
@@ -163,11 +166,14 @@ def test_encoder_block_vit_b(name, g, ws, Bm, r, rho, scale_w):
     ow = oracle.BlockWeights(**wt)
     for b in range(x.shape[0]):
         ref = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, r, keep[b])
-        assert_close(got[b] - x[b], ref - x[b], f"{name}: block delta b={b}")
+        assert_close(got[b] - x[b], ref - x[b], f"{name}: block delta b={b}", stored=ref, updates=2)
         attn_only = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, r, np.zeros(0, np.int32))
         rest = np.setdiff1d(np.arange(g * g), keep[b])
+        if rest.size == 0:
+            continue
         assert_close(got[b].reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest],
-                     attn_only.reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest], f"{name}: attention-only rows b={b}")
+                     attn_only.reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest], f"{name}: attention-only rows b={b}",
+                     stored=attn_only.reshape(g * g, -1)[rest], scale=np.abs(ref - x[b]).max())
 
 
 def test_encoder_block_vit_h_dims():
@@ -178,7 +184,7 @@ def test_encoder_block_vit_h_dims():
         wt, x, keep, K = make_block_case(31, 1, 28, shape, ws, 0.4)
         got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4)
         ref = oracle.encoder_block(x[0], oracle.BlockWeights(**wt), shape.heads, ws, 4, Bm, 0.4, keep[0])
-        assert_close(got[0] - x[0], ref - x[0], f"ViT-H block ws={ws}")
+        assert_close(got[0] - x[0], ref - x[0], f"ViT-H block ws={ws}", stored=ref, updates=2)
 
 
 # ------------------------------------------------------------------ block stack
@@ -219,11 +225,11 @@ def test_encoder_forward_small_stack():
         thr = np.sort(sc_ref)[::-1][K - 1]
         assert np.all(np.abs(sc_ref[diff] - thr) <= 1e-4 * thr), "keep-sets differ away from the threshold"
         if diff.size == 0:
-            assert_close(got[b] - x[b], ref - x[b], f"encoder stack b={b}")
+            assert_close(got[b] - x[b], ref - x[b], f"encoder stack b={b}", stored=ref, updates=6)
         else:                                                      # rerun the oracle on the GPU's (valid) keep-set
             y = x[b]
             for i, w in enumerate(wts):
                 glob = i in shape.global_blocks
                 y = oracle.encoder_block(y, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
                                          128 if glob else 32, r, keep_gpu[b])
-            assert_close(got[b] - x[b], y - x[b], f"encoder stack b={b} (threshold tie)")
+            assert_close(got[b] - x[b], y - x[b], f"encoder stack b={b} (threshold tie)", stored=y, updates=6)
