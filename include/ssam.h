@@ -225,14 +225,18 @@ int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cf
  * where is_global[i] != 0, cfg_global.  weights, is_global: host arrays of
  * n_blocks entries.  keep_idx dev int32 [B][K] is written and then read;
  * scores dev fp32 [B][N] likewise.  Tables as for ssam_encoder_block.
- * workspace >= ssam_encoder_workspace_bytes(cfg_local, cfg_global). */
+ * workspace >= ssam_encoder_workspace_bytes(cfg_local, cfg_global).
+ * qkv_events: optional instrumentation, host array of 2*n_blocks hipEvent_t
+ * (NULL = none): events [2i] and [2i+1] are recorded on the stream right before
+ * and right after block i's qkv contraction, so that a benchmark can time that
+ * kernel inside its own timed region. */
 size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global);
 int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
                          const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,
                          const int32_t *window_table, const int32_t *sigma_window,
                          const int32_t *global_table, const int32_t *sigma_global,
                          float *scores, int32_t *keep_idx,
-                         void *workspace, size_t workspace_bytes, void *stream);
+                         void *workspace, size_t workspace_bytes, void **qkv_events, void *stream);
 
 #ifdef __cplusplus
 }

@@ -272,11 +272,21 @@ def ssam_encoder_workspace_bytes(cfg_local, cfg_global) -> int:
                                               C.byref(cfg_global) if cfg_global is not None else None)
 
 
+class EncoderPlan:
+    """Host-side argument block of ssam_encoder_forward, marshalled once and reused."""
+
+    def __init__(self, wstructs, is_global):
+        self.n = len(wstructs)
+        self.weights = (BlockWeights * self.n)(*wstructs)
+        self.flags = (C.c_uint8 * self.n)(*[1 if f else 0 for f in is_global])
+
+
 def ssam_encoder_forward(x, wstructs, is_global, cfg_local, cfg_global, window_table, sigma_window,
-                         global_table, sigma_global, scores, keep_idx, workspace):
-    n = len(wstructs)
-    arr = (BlockWeights * n)(*wstructs)
-    flags = (C.c_uint8 * n)(*[1 if f else 0 for f in is_global])
+                         global_table, sigma_global, scores, keep_idx, workspace, qkv_events=None, plan=None):
+    """qkv_events: optional ctypes array of 2*n_blocks hipEvent_t handles (c_void_p)."""
+    if plan is None:
+        plan = EncoderPlan(wstructs, is_global)
+    n, arr, flags = plan.n, plan.weights, plan.flags
     _check("ssam_encoder_forward", lib().ssam_encoder_forward(
         _bf(x, "x"), arr, flags, C.c_int(n),
         C.byref(cfg_local) if cfg_local is not None else None,
@@ -284,5 +294,5 @@ def ssam_encoder_forward(x, wstructs, is_global, cfg_local, cfg_global, window_t
         _i32(window_table, "window_table"), _i32(sigma_window, "sigma_window"),
         _i32(global_table, "global_table"), _i32(sigma_global, "sigma_global"),
         _f32(scores, "scores"), _i32(keep_idx, "keep_idx"),
-        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), qkv_events, _stream()))
     return x

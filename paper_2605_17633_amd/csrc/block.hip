@@ -76,9 +76,9 @@ extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
     return attn > mlp ? attn : mlp;
 }
 
-extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
-                                  const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
-                                  void *workspace, size_t workspace_bytes, void *stream)
+static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
+                              const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
+                              void *workspace, size_t workspace_bytes, void **qkv_events, void *stream)
 {
     BlockGeom g;
     if (!x || !w || !gather_table || !sigma || !keep_idx || !workspace || !block_geom(cfg, g)) return SSAM_EINVAL;
@@ -96,8 +96,10 @@ extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ss
     int rc = ssam_ln_gather(x, gather_table, 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
+    if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
     rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, SSAM_EPI_BIAS, none, 0, st);
     if (rc != SSAM_OK) return rc;
+    if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
     rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, u,
                                B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
@@ -108,6 +110,13 @@ extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ss
     if (rc != SSAM_OK) return rc;
     return ssam_routed_mlp(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2,
                            B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);
+}
+
+extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
+                                  const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, stream);
 }
 
 extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global)
@@ -125,7 +134,7 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
                                     const int32_t *window_table, const int32_t *sigma_window,
                                     const int32_t *global_table, const int32_t *sigma_global,
                                     float *scores, int32_t *keep_idx,
-                                    void *workspace, size_t workspace_bytes, void *stream)
+                                    void *workspace, size_t workspace_bytes, void **qkv_events, void *stream)
 {
     if (!x || !weights || !is_global || n_blocks <= 0 || !scores || !keep_idx || !workspace) return SSAM_EINVAL;
     bool any_local = false, any_global = false;
@@ -145,9 +154,10 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
     rc = ssam_select_tokens(scores, keep_idx, c0->B, c0->g * c0->g, c0->K, stream);
     if (rc != SSAM_OK) return rc;
     for (int i = 0; i < n_blocks; ++i) {
+        void **ev = qkv_events ? qkv_events + 2 * i : nullptr;
         rc = is_global[i]
-                 ? ssam_encoder_block(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, stream)
-                 : ssam_encoder_block(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, stream);
+                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, ev, stream)
+                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, ev, stream);
         if (rc != SSAM_OK) return rc;
     }
     return SSAM_OK;
