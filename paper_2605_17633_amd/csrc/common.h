@@ -15,6 +15,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define SSAM_WAVE 64
 
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not drain the
+// global-memory counter, so prefetches of later K slabs stay in flight across it.
+#define LDS_BARRIER()                                                         \
+    do {                                                                      \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");       \
+        __builtin_amdgcn_s_barrier();                                         \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");       \
+    } while (0)
+
 #define SSAM_CHECK_LAUNCH()                                   \
     do {                                                      \
         if (hipGetLastError() != hipSuccess) return SSAM_EHIP; \

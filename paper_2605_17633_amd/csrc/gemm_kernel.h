@@ -1,18 +1,20 @@
-// bf16 NT GEMM for gfx950: C = epilogue(A[M][K] * W[N][K]^T + bias), fp32
-// accumulation on the 32x32x16 bf16 MFMA.  Serves the block's qkv / proj / fc1 /
-// fc2 layers (the dense contractions of the SAM block; the routed MLP of
-// Sec. 4.2 reaches it with the gathered keep-set rows as A).
+// bf16 NT GEMM for gfx950: C = epilogue(A[M][K] * W[N][K]^T + bias), fp32 accumulation on the
+// 32x32x16 bf16 MFMA.  Serves the block's qkv / proj / fc1 / fc2 layers (the dense contractions
+// of the SAM block; the routed MLP of Sec. 4.2 reaches it with the gathered keep-set rows as A).
 //
-// Workgroup = 256 threads = 4 waves in a 2x2 grid over a BM x BN tile; each wave
-// owns (BM/2) x (BN/2) as 32x32 MFMA tiles.  K is consumed in slabs of 64:
-// global -> registers (prefetch of the next slab while the current one is
-// multiplied) -> LDS (double buffered, 16-byte chunks XOR-swizzled by row so
-// that the 8 lanes of a ds_read_b128 phase touch 8 different bank groups).
-// MFMA operand layout (32x32x16): lane l feeds row (l & 31), k-chunk (l >> 5)
-// of 8 consecutive bf16; the result register r of lane l is
-// C[8*(r/4) + 4*(l>>5) + (r&3)][l & 31] with rows from operand a, columns from b.
-// The epilogue stages 32-row slices of the fp32 result through LDS so that each
-// lane finishes 8 consecutive columns and issues 16-byte global accesses.
+// Workgroup = 256 threads = 4 waves in a 2x2 grid over a BM x BN tile; each wave owns
+// (BM/2) x (BN/2) as 32x32 MFMA tiles.  K is consumed in slabs of 64: global -> registers
+// (prefetch of the next slab) -> LDS (double buffered; 16-byte chunks XOR-swizzled so that both
+// the staging writes and the ds_read_b128 fragment reads are bank-conflict free).  Fragments are
+// double buffered in registers and the instruction mix is pinned with sched_group_barrier so that
+// LDS reads, global loads and LDS writes sit between MFMAs instead of in front of them; the
+// per-slab barrier orders LDS traffic only, so global prefetches stay in flight across it.
+// MFMA layout (32x32x16): lane l feeds row (l & 31), k-chunk (l >> 5); result register r of lane l
+// is C[8*(r/4) + 4*(l>>5) + (r&3)][l & 31], rows from operand a (activations), columns from b (W).
+// The epilogue stages 32-row slices of the fp32 result through LDS so that each lane finishes 8
+// consecutive columns and issues 16-byte global accesses.
+// Tiles are dealt so that each XCD (its own L2) works on a contiguous run of tiles, ordered in
+// bands of 8 tile rows: workgroups that run together share A and W panels.
 #pragma once
 
 #include "common.h"
@@ -36,7 +38,9 @@ constexpr size_t gemm_lds_bytes()
 }
 
 // element offset of 16-byte chunk c (0..7) of row `row` in a [rows][64] bf16 slab
-__device__ __forceinline__ int gemm_swz(int row, int c) { return row * GEMM_BK + ((c ^ (row & 7)) << 3); }
+__device__ __forceinline__ int gemm_swz(int row, int c) { return row * GEMM_BK + ((c ^ ((row >> 1) & 7)) << 3); }
+
+#define GEMM_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
 template <int BM, int BN, int EPI>
 __global__ void __launch_bounds__(GEMM_THREADS)
@@ -46,13 +50,13 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
     constexpr int A_LOADS = BM * 8 / GEMM_THREADS, B_LOADS = BN * 8 / GEMM_THREADS;
     constexpr int GROUP_M = 8;
+    constexpr int NM = MT * NT, NR = MT + NT, NL = A_LOADS + B_LOADS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16 *As = reinterpret_cast<bf16 *>(smem);                 // [2][BM*64]
     bf16 *Bs = As + 2 * BM * GEMM_BK;                          // [2][BN*64]
 
-    // ---- tile assignment: workgroups are dealt round-robin to the 8 XCDs, so
-    // give each XCD a contiguous run of tiles (its own L2 then sees neighbouring
-    // A and W panels), ordered in bands of GROUP_M tile rows.
+    // ---- tile assignment: workgroups are dealt round-robin to the 8 XCDs; XCD x takes the tiles
+    // x*per_xcd .. (x+1)*per_xcd-1 of the band order
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -67,6 +71,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
     const int l32 = lane & 31, half = lane >> 5;
+    const int nk = K / GEMM_BK;
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -77,64 +82,90 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     u32x4 ra[A_LOADS], rb[B_LOADS];
-    const int nk = K / GEMM_BK;
+    bf16x8 af[2][MT], bfr[2][NT];
 
-#define GEMM_LOAD_GLOBAL(kt_)                                                                          \
-    {                                                                                                  \
-        const int k0_ = (kt_) * GEMM_BK;                                                               \
-        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
-        {                                                                                              \
-            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
-            int m = min(m0 + row, M - 1); /* rows past M repeat the last row; never stored */         \
-            ra[i] = *reinterpret_cast<const u32x4 *>(A + (long)m * K + k0_ + c * 8);                   \
-        }                                                                                              \
-        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                            \
-        {                                                                                              \
-            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
-            rb[i] = *reinterpret_cast<const u32x4 *>(W + (long)(n0 + row) * K + k0_ + c * 8);          \
-        }                                                                                              \
+    // staging: thread owns chunk c0 of rows r0 + 32*i of both operands
+    const int r0 = tid >> 3, c0 = tid & 7;
+    const bf16 *ga[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i)          // rows past M repeat the last row; their results are never stored
+        ga[i] = A + (long)min(m0 + r0 + 32 * i, M - 1) * K + c0 * 8;
+    const bf16 *gb = W + (long)(n0 + r0) * K + c0 * 8;
+    const int lst = gemm_swz(r0, c0);          // + i*32*64: rows 32 apart share the swizzle term
+    const int fa0 = (wm + l32) * GEMM_BK, fb0 = (wn + l32) * GEMM_BK;
+    const int sw = (l32 >> 1) & 7;
+
+#define GEMM_LOAD_GLOBAL(kt_)                                                                         \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
+            ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + (kt_) * GEMM_BK);                        \
+        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
+            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * 32 * K + (kt_) * GEMM_BK);        \
     }
-#define GEMM_STORE_LDS(buf_)                                                                           \
-    {                                                                                                  \
-        bf16 *as_ = As + (buf_) * BM * GEMM_BK, *bs_ = Bs + (buf_) * BN * GEMM_BK;                     \
-        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                            \
-        {                                                                                              \
-            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
-            *reinterpret_cast<u32x4 *>(as_ + gemm_swz(row, c)) = ra[i];                                \
-        }                                                                                              \
-        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                            \
-        {                                                                                              \
-            int id = tid + i * GEMM_THREADS, row = id >> 3, c = id & 7;                                \
-            *reinterpret_cast<u32x4 *>(bs_ + gemm_swz(row, c)) = rb[i];                                \
-        }                                                                                              \
+#define GEMM_STORE_LDS(buf_)                                                                          \
+    {                                                                                                 \
+        bf16 *as_ = As + (buf_) * BM * GEMM_BK + lst, *bs_ = Bs + (buf_) * BN * GEMM_BK + lst;        \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
+            *reinterpret_cast<u32x4 *>(as_ + i * 32 * GEMM_BK) = ra[i];                               \
+        _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
+            *reinterpret_cast<u32x4 *>(bs_ + i * 32 * GEMM_BK) = rb[i];                               \
+    }
+#define GEMM_LOAD_FRAGS(buf_, ks_, slot_)                                                             \
+    {                                                                                                 \
+        const int co_ = (((ks_) * 2 + half) ^ sw) << 3;                                               \
+        const bf16 *as_ = As + (buf_) * BM * GEMM_BK + fa0 + co_;                                     \
+        const bf16 *bs_ = Bs + (buf_) * BN * GEMM_BK + fb0 + co_;                                     \
+        _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                \
+            af[slot_][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * GEMM_BK);                 \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                \
+            bfr[slot_][j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 32 * GEMM_BK);                \
+    }
+#define GEMM_MFMAS(slot_)                                                                             \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < NT; ++j)                                            \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], bfr[slot_][j], acc[i][j], 0, 0, 0); \
     }
 
     GEMM_LOAD_GLOBAL(0)
     GEMM_STORE_LDS(0)
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) GEMM_LOAD_GLOBAL(kt + 1)
-        const bf16 *as = As + buf * BM * GEMM_BK, *bs = Bs + buf * BN * GEMM_BK;
+    LDS_BARRIER();
+    int buf = 0;
+    for (int kt = 0; kt < nk - 1; ++kt, buf ^= 1) {
+        GEMM_LOAD_FRAGS(buf, 0, 0)
+        GEMM_LOAD_GLOBAL(kt + 1)
+        GEMM_LOAD_FRAGS(buf, 1, 1)
+        GEMM_MFMAS(0)
+        GEMM_LOAD_FRAGS(buf, 2, 0)
+        GEMM_MFMAS(1)
+        GEMM_LOAD_FRAGS(buf, 3, 1)
+        GEMM_MFMAS(0)
+        GEMM_MFMAS(1)
+        GEMM_STORE_LDS(buf ^ 1)
+        // issue order: fragments of k-step 0; then per k-step its MFMAs with the next step's LDS reads,
+        // the next slab's global loads (step 0) and LDS writes (step 3) slotted in between
+        GEMM_SGB(0x100, NR);
 #pragma unroll
-        for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
-            bf16x8 af[MT], bfr[NT];
-            const int c = ks * 2 + half;
+        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); if (i < NL) GEMM_SGB(0x020, 1); }
+        if (NL > NM) GEMM_SGB(0x020, NL - NM);
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(as + gemm_swz(wm + i * 32 + l32, c));
+        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); }
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + gemm_swz(wn + j * 32 + l32, c));
+        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); }
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) GEMM_STORE_LDS(buf ^ 1)
-        __syncthreads();
+        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NL) GEMM_SGB(0x200, 1); }
+        if (NL > NM) GEMM_SGB(0x200, NL - NM);
+        LDS_BARRIER();
+    }
+    {
+        GEMM_LOAD_FRAGS(buf, 0, 0)
+        GEMM_LOAD_FRAGS(buf, 1, 1)
+        GEMM_MFMAS(0)
+        GEMM_LOAD_FRAGS(buf, 2, 0)
+        GEMM_MFMAS(1)
+        GEMM_LOAD_FRAGS(buf, 3, 1)
+        GEMM_MFMAS(0)
+        GEMM_MFMAS(1)
     }
 
     // ---- epilogue: 32-row slices through a per-wave fp32 LDS region
