@@ -4,22 +4,30 @@
 // scan position to its spatial cell for the bias lookup.
 //
 // Formulation.  Scores are computed transposed, S^T = K Q^T, on the 32x32x16 bf16
-// MFMA: the Q fragments (operand b) stay in registers for the whole kernel, K
+// MFMA: the Q fragments (operand b) stay in registers for the whole problem, K
 // rows come from LDS (operand a).  In the result layout every lane owns ONE
 // query (column l & 31) and 16 of the 32 keys of a block, so the softmax row
 // statistics are per-lane scalars: the row maximum needs a single exchange with
 // lane l^32, the row sum none until the end.  exp(S^T) converted to bf16 is
-// already in the operand-b layout of the second product O^T = V^T P^T; the
-// operand-a fragments are read from a transposed copy of V in LDS with the key
-// order the result layout dictates (contraction slot e of half-wave hf of MFMA
-// t  <->  key 16t + 8(e/4) + 4hf + (e&3)).
+// already in the operand-b layout of the second product O^T = V^T P^T.  Its
+// operand-a fragments (8 keys of one feature column per lane, in the key order
+// the result layout dictates: contraction slot e of half-wave hf of MFMA t <->
+// key 16t + 8(e/4) + 4hf + (e&3)) come from the row-major V rows in LDS through
+// the transposing LDS read of gfx950 (ds_read_b64_tr_b16: a 16-lane group reads
+// 4 rows x 16 columns and every lane receives one column), so V is staged
+// exactly like K and never transposed in memory.
+// Key blocks are processed in chunks of up to four (128 keys): all score MFMAs
+// of the chunk first, one max / one rescale of the running output per chunk,
+// then all P V MFMAs, so that the matrix pipe sees long runs of independent work.
 // Bias: per wave, U = Q R^T is formed once with the MFMA for both tables and
 // scattered into per-query rows B^H[q][key_row], B^W[q][key_col] in LDS
 // (pre-multiplied by log2 e); the inner loop adds two table look-ups per score.
 //
 // Two launch shapes:
-//   window kernel: one workgroup per (window, head), one wave per 32-query tile
-//                  (= mask tile of 32), the window's whole K and V^T in LDS;
+//   window kernel: persistent workgroups looping over (window, head) problems, one
+//                  wave per 32-query tile (= mask tile of 32), the window's whole K
+//                  and V in LDS, the next problem's Q/K/V prefetched into registers,
+//                  the rel-pos tables resident in LDS;
 //   global kernel: one workgroup per (128-query mask tile, image, head), 4 waves,
 //                  active 128-key tiles streamed through LDS with register prefetch.
 #include "common.h"
@@ -42,7 +50,7 @@ template <int D>
 struct AttnCfg {
     static constexpr int KS = D / 16;            // k-steps of the score product
     static constexpr int DT = (D + 31) / 32;     // 32-row tiles of O^T
-    static constexpr int KSTR = D + 8;           // K row stride in LDS (elements): odd in 16-byte units
+    static constexpr int KSTR = D + 8;           // row stride in LDS (elements): odd in 16-byte units
     static constexpr int CH = D / 8;             // 16-byte chunks per row
 };
 
@@ -53,10 +61,25 @@ struct WaveState {
     float m, l;
 };
 
-// Bias rows for the wave's 32 queries: th[q*ts + p] = log2e * q . rel_h[row(q)-p+w-1], tw likewise.
 template <int D>
-__device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w,
-                                                int w, int qrow, int qcol, float *th, float *tw, int ts)
+__device__ __forceinline__ void init_state(WaveState<D> &st)
+{
+#pragma unroll
+    for (int dt = 0; dt < AttnCfg<D>::DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
+    st.m = -INFINITY;
+    st.l = 0.f;
+}
+
+// Bias rows for the wave's 32 queries, one table row of 2*ts floats per query:
+//   tq[q*2*ts + p]      = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
+//   tq[q*2*ts + ts + p] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
+// rel tables: rows of `rstr` elements, from global memory (rstr = D) or from a zero-padded LDS copy.
+template <int D>
+__device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr,
+                                                bool rows_padded, int w, int qrow, int qcol,
+                                                float *tq, int ts)
 {
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int nrel = 2 * w - 1;
@@ -68,15 +91,16 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
 #pragma unroll
             for (int r = 0; r < 16; ++r) u[r] = 0.f;
             const int mrow = mt * 32 + l32;
+            const bool ok = rows_padded || mrow < nrel;
 #pragma unroll
             for (int ks = 0; ks < AttnCfg<D>::KS; ++ks) {
                 bf16x8 a;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = (bf16)0.f;
-                if (mrow < nrel) a = *reinterpret_cast<const bf16x8 *>(rel + (long)mrow * D + ks * 16 + half * 8);
+                if (ok) a = *reinterpret_cast<const bf16x8 *>(rel + (long)mrow * rstr + ks * 16 + half * 8);
                 u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], u, 0, 0, 0);
             }
-            float *dst = (tab ? tw : th) + l32 * ts;
+            float *dst = tq + l32 * 2 * ts + (tab ? ts : 0);
             const int qpos = tab ? qcol : qrow;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -88,70 +112,99 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
     }
 }
 
-// One 32-key block against the wave's 32 queries.
-//   kblk: LDS, row-major K rows of this block ([32][KSTR])
-//   vt:   LDS, V^T with `vstr` elements per feature row; vcol0 = column of the block's first key
-//   krc:  LDS, per key of this block (row | col << 16) of its spatial cell
-//   key0: scan position of the block's first key (for the S bound)
-template <int D>
-__device__ __forceinline__ void attn_block_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *kblk,
-                                                const bf16 *vt, int vstr, int vcol0, const uint32_t *krc,
-                                                int key0, int S, float scale_log2e,
-                                                const float *th, const float *tw)
+// A chunk of nb (1..NB, wave-uniform) 32-key blocks against the wave's 32 queries.
+//   Ks, Vs: LDS, row-major rows ([keys][KSTR]); blk[b]: index of the chunk's b-th block in them
+//   krc:    LDS, per key the byte offsets of its bias entries in a query's table row:
+//           low half = 4*row, high half = 4*(ts + col); indexed like Ks
+//   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
+//   tq:     this lane's query row of the bias table
+template <int D, int NB, bool RAGGED>
+__device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
+                                                const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
+                                                int S, float scale_log2e, const float *tq)
 {
     using C = AttnCfg<D>;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
-    f32x16 s;
+    f32x16 s[NB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(kblk + l32 * C::KSTR + ks * 16 + half * 8);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
+            for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
+            const bf16 *kblk = Ks + blk[b] * 32 * C::KSTR + l32 * C::KSTR + half * 8;
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) {
+                bf16x8 a = *reinterpret_cast<const bf16x8 *>(kblk + ks * 16);
+                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[b], 0, 0, 0);
+            }
+        }
     }
     float mx = st.m;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const u32x4 rc = *reinterpret_cast<const u32x4 *>(krc + 8 * g + 4 * half);
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
+            const unsigned char *tqb = reinterpret_cast<const unsigned char *>(tq);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            const int kl = 8 * g + 4 * half + e;
-            const uint32_t c = rc[e];
-            float val = s[r] * scale_log2e + th[c & 0xffffu] + tw[c >> 16];
-            val = (key0 + kl < S) ? val : -INFINITY;
-            s[r] = val;
-            mx = fmaxf(mx, val);
+            for (int g = 0; g < 4; ++g) {
+                const u32x4 rc = *reinterpret_cast<const u32x4 *>(krc + blk[b] * 32 + 8 * g + 4 * half);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * g + e;
+                    const uint32_t c = rc[e];
+                    const float bh = *reinterpret_cast<const float *>(tqb + (c & 0xffffu));
+                    const float bw = *reinterpret_cast<const float *>(tqb + (c >> 16));
+                    float val = s[b][r] * scale_log2e + bh + bw;
+                    if (RAGGED) val = (key0[b] + 8 * g + 4 * half + e < S) ? val : -INFINITY;
+                    s[b][r] = val;
+                    mx = fmaxf(mx, val);
+                }
+            }
         }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = exp2f(st.m - mx);      // first block: exp2(-inf) = 0
+    const float alpha = __builtin_amdgcn_exp2f(st.m - mx);      // first chunk: exp2(-inf) = 0
     st.m = mx;
     float psum = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        s[r] = exp2f(s[r] - mx);
-        psum += s[r];
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[b][r] = __builtin_amdgcn_exp2f(s[b][r] - mx);
+                psum += s[b][r];
+            }
+        }
     }
     st.l = st.l * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {       // the running maximum moved for some query
 #pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
+        for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
+            for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
+    }
+    // transposing read: lane li of a 16-lane group points at row (li >> 2), column chunk (li & 3) of a
+    // 4-key x 16-feature block and receives the 4 keys of feature column li
+    const int li = lane & 15, fblk = (lane >> 4) & 1;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        bf16x8 p;
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
+            const bf16 *vblk = Vs + blk[b] * 32 * C::KSTR + (4 * half + (li >> 2)) * C::KSTR;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) p[e] = (bf16)s[8 * t + e];
+            for (int t = 0; t < 2; ++t) {
+                bf16x8 p;
 #pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt) {
-            int dd = dt * 32 + l32;
-            dd = dd < D ? dd : D - 1;            // rows past D repeat the last row; their outputs are dropped
-            const bf16 *vrow = vt + dd * vstr + vcol0 + 16 * t + 4 * half;
-            bf16x4 v0 = *reinterpret_cast<const bf16x4 *>(vrow);
-            bf16x4 v1 = *reinterpret_cast<const bf16x4 *>(vrow + 8);
-            bf16x8 a = { v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3] };
-            st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p, st.o[dt], 0, 0, 0);
+                for (int e = 0; e < 8; ++e) p[e] = (bf16)s[b][8 * t + e];
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt) {
+                    int col = dt * 32 + 16 * fblk + 4 * (li & 3);
+                    col = col <= D - 4 ? col : D - 4;    // feature columns past D re-read the last ones; outputs dropped
+                    const bf16 *v0p = vblk + 16 * t * C::KSTR + col;
+                    bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p));
+                    bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p + 8 * C::KSTR));
+                    bf16x8 a = { v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3] };
+                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p, st.o[dt], 0, 0, 0);
+                }
+            }
         }
     }
 }
@@ -165,15 +218,19 @@ __device__ __forceinline__ void load_q_frags(bf16x8 *qf, const bf16 *qrow)
         qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + ks * 16 + half * 8);
 }
 
+// Normalise the wave's 32 x D output tile and write it out.  The accumulators hold O^T (lane = query,
+// registers = 4-feature groups); the tile goes through a per-wave LDS staging area ([32][KSTR] bf16) so
+// that the global stores are 16 bytes per lane and cover whole rows.  `stage` may overlay LDS that only
+// this wave used (its bias rows).  orow0: output row of the wave's first query; nrows: valid queries.
 template <int D>
-__device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *orow, bool valid)
+__device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, bf16 *orow0, long out_stride, int nrows)
 {
-    const int half = (threadIdx.x & 63) >> 5;
+    using C = AttnCfg<D>;
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const float l = st.l + __shfl_xor(st.l, 32, 64);
     const float inv = 1.0f / l;
-    if (!valid) return;
 #pragma unroll
-    for (int dt = 0; dt < AttnCfg<D>::DT; ++dt)
+    for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             int dd = dt * 32 + 8 * g + 4 * half;
@@ -181,9 +238,20 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *orow, b
                 uint2 pk;
                 pk.x = pack_bf16x2(st.o[dt][4 * g + 0] * inv, st.o[dt][4 * g + 1] * inv);
                 pk.y = pack_bf16x2(st.o[dt][4 * g + 2] * inv, st.o[dt][4 * g + 3] * inv);
-                *reinterpret_cast<uint2 *>(orow + dd) = pk;
+                *reinterpret_cast<uint2 *>(stage + l32 * C::KSTR + dd) = pk;
             }
         }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // LDS is in order per wave; keep the compiler from reordering
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int i = 0; i < (32 * C::CH + 63) / 64; ++i) {
+        int id = lane + 64 * i, row = id / C::CH, c = id % C::CH;
+        if (id < 32 * C::CH && row < nrows) {
+            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * C::KSTR + c * 8);
+            *reinterpret_cast<u32x4 *>(orow0 + (long)row * out_stride + c * 8) = v;
+        }
+    }
 }
 
 __device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int S, int w)
@@ -193,71 +261,130 @@ __device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int
     return (uint32_t)(cell / w) | ((uint32_t)(cell % w) << 16);
 }
 
+// the same as byte offsets into a query's bias table row (th part, then tw part at +ts floats)
+__device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p, int S, int w, int ts)
+{
+    uint32_t rc = key_row_col(sigma, p, S, w);
+    return (4u * (rc & 0xffffu)) | ((4u * ((uint32_t)ts + (rc >> 16))) << 16);
+}
+
+// per-wave LDS scratch: the bias rows of its 32 queries, later overlaid by its output staging tile
+template <int D>
+__host__ __device__ inline int wave_scratch_bytes(int ts)
+{
+    int bias = 32 * 2 * ts * 4, stage = 32 * AttnCfg<D>::KSTR * 2;
+    return ((bias > stage ? bias : stage) + 15) & ~15;
+}
+
 // ------------------------------------------------------------------ window kernel
+inline int window_rel_rows(int w) { return ((2 * w - 1 + 31) / 32) * 32; }
+
 template <int D>
 size_t window_lds_bytes(int nqb, int w)
 {
     int SP = nqb * 32, ts = w | 1;
-    return (size_t)SP * AttnCfg<D>::KSTR * 2 + (size_t)D * (SP + 4) * 2 + (size_t)nqb * 32 * 2 * ts * 4 + (size_t)SP * 4;
+    return (size_t)2 * SP * AttnCfg<D>::KSTR * 2 + (size_t)2 * window_rel_rows(w) * AttnCfg<D>::KSTR * 2 +
+           (size_t)nqb * wave_scratch_bytes<D>(ts) + (size_t)SP * 4;
 }
+
+constexpr int WIN_NB = 2;            // key blocks per softmax chunk in the window kernel (register budget: 2 waves per SIMD)
+constexpr int WIN_MAX_LOADS = 5;     // 16-byte K (and V) chunks per thread: 224 keys * 10 chunks / 448 threads
 
 template <int D>
 __global__ void __launch_bounds__(448)
-attn_window_kernel(AttnParams P)
+attn_window_kernel(AttnParams P, int n_problems)
 {
     using C = AttnCfg<D>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int nqb = blockDim.x >> 6, SP = nqb * 32, vstr = SP + 4, ts = P.w | 1;
+    const int nqb = blockDim.x >> 6, SP = nqb * 32, ts = P.w | 1;
+    const int nrel = 2 * P.w - 1, rrows = ((nrel + 31) / 32) * 32;
     bf16 *Ks = reinterpret_cast<bf16 *>(smem);
-    bf16 *Vt = Ks + SP * C::KSTR;
-    float *T = reinterpret_cast<float *>(Vt + D * vstr);
-    uint32_t *krc = reinterpret_cast<uint32_t *>(T + nqb * 32 * 2 * ts);
+    bf16 *Vs = Ks + SP * C::KSTR;
+    bf16 *Rh = Vs + SP * C::KSTR;                 // rel-pos tables, zero-padded to rrows rows
+    bf16 *Rw = Rh + rrows * C::KSTR;
+    unsigned char *T = reinterpret_cast<unsigned char *>(Rw + rrows * C::KSTR);
+    const int wsb = wave_scratch_bytes<D>(ts);
+    uint32_t *krc = reinterpret_cast<uint32_t *>(T + nqb * wsb);
 
-    const int grp = blockIdx.x / P.h, head = blockIdx.x % P.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31;
     const int S = P.S;
-    const long base = (long)grp * S * P.row_stride + (long)head * D;
+    const int nloads = (SP * C::CH + blockDim.x - 1) / blockDim.x;     // <= WIN_MAX_LOADS (checked on the host)
 
-    // stage K rows and V^T (pad keys are zero so that 0-probabilities meet finite values)
-    for (int id = tid; id < SP * C::CH; id += blockDim.x) {
-        int key = id / C::CH, c = id % C::CH;
-        u32x4 kv = { 0, 0, 0, 0 }, vv = { 0, 0, 0, 0 };
-        if (key < S) {
-            kv = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8);
-            vv = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8);
-        }
-        *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = kv;
-        const bf16x8 ve = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * vstr + key] = ve[e];
+    // problem-independent state: scan-order geometry and the rel-pos tables
+    for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(P.sigma, p, S, P.w, ts);
+    for (int id = tid; id < 2 * rrows * C::CH; id += blockDim.x) {
+        int tab = id / (rrows * C::CH), rem = id % (rrows * C::CH), row = rem / C::CH, c = rem % C::CH;
+        u32x4 v = { 0, 0, 0, 0 };
+        if (row < nrel) v = *reinterpret_cast<const u32x4 *>((tab ? P.rel_w : P.rel_h) + (long)row * D + c * 8);
+        *reinterpret_cast<u32x4 *>((tab ? Rw : Rh) + row * C::KSTR + c * 8) = v;
     }
-    for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_row_col(P.sigma, p, S, P.w);
-
     const int q0 = wave * 32, qpos = q0 + l32;
     const int qclamp = qpos < S ? qpos : S - 1;
-    bf16x8 qf[C::KS];
-    load_q_frags<D>(qf, P.q + base + (long)qclamp * P.row_stride);
     const uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
-    float *th = T + wave * 32 * 2 * ts, *tw = th + 32 * ts;
-    build_bias_rows<D>(qf, P.rel_h, P.rel_w, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), th, tw, ts);
-    __syncthreads();
-
-    WaveState<D> st;
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
-    st.m = -INFINITY;
-    st.l = 0.f;
-
-    // active key tiles of query tile `wave`: the dense prefix, then the diagonal
+    float *tq = reinterpret_cast<float *>(T + wave * wsb);
     const int nact = P.n_pre + (wave >= P.n_pre ? 1 : 0);
-    for (int a = 0; a < nact; ++a) {
-        const int kb = a < P.n_pre ? a : wave;
-        attn_block_step<D>(st, qf, Ks + kb * 32 * C::KSTR, Vt, vstr, kb * 32, krc + kb * 32, kb * 32, S,
-                           P.scale_log2e, th + l32 * ts, tw + l32 * ts);
+
+    u32x4 rk[WIN_MAX_LOADS], rv[WIN_MAX_LOADS];
+    bf16x8 qf[C::KS], qnext[C::KS];
+
+#define WIN_PREFETCH(prob_)                                                                             \
+    {                                                                                                   \
+        const int g_ = (prob_) / P.h, hd_ = (prob_) % P.h;                                              \
+        const long base_ = (long)g_ * S * P.row_stride + (long)hd_ * D;                                 \
+        _Pragma("unroll") for (int i = 0; i < WIN_MAX_LOADS; ++i)                                       \
+        {                                                                                               \
+            int id = tid + i * (int)blockDim.x, key = id / C::CH, c = id % C::CH;                       \
+            key = key < S ? key : S - 1; /* pad keys repeat the last row: finite values, masked */      \
+            if (i < nloads) {                                                                           \
+                rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base_ + (long)key * P.row_stride + c * 8); \
+                rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base_ + (long)key * P.row_stride + c * 8); \
+            }                                                                                           \
+        }                                                                                               \
+        load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);                              \
     }
-    finish_and_store<D>(st, P.out + ((long)grp * S + qclamp) * ((long)P.h * D) + (long)head * D, qpos < S);
+
+    int prob = blockIdx.x;
+    if (prob < n_problems) WIN_PREFETCH(prob)
+    for (; prob < n_problems; prob += gridDim.x) {
+        const int grp = prob / P.h, head = prob % P.h;
+        LDS_BARRIER();                            // every wave is done with the previous problem's LDS (output stores stay in flight)
+#pragma unroll
+        for (int i = 0; i < WIN_MAX_LOADS; ++i) {
+            int id = tid + i * (int)blockDim.x, key = id / C::CH, c = id % C::CH;
+            if (i < nloads && id < SP * C::CH) {
+                *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = rk[i];
+                *reinterpret_cast<u32x4 *>(Vs + key * C::KSTR + c * 8) = rv[i];
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = qnext[ks];
+        if (prob + (int)gridDim.x < n_problems) WIN_PREFETCH(prob + (int)gridDim.x)
+        build_bias_rows<D>(qf, Rh, Rw, C::KSTR, true, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+        LDS_BARRIER();
+
+        WaveState<D> st;
+        init_state<D>(st);
+        // active key tiles of query tile `wave`: the dense prefix, then the diagonal; chunks of four
+        for (int a0 = 0; a0 < nact; a0 += WIN_NB) {
+            int blk[WIN_NB], key0[WIN_NB];
+#pragma unroll
+            for (int b = 0; b < WIN_NB; ++b) {
+                int a = a0 + b;
+                blk[b] = a < P.n_pre ? a : wave;
+                key0[b] = blk[b] * 32;
+            }
+            // only the last 32-key tile of the window can cross S
+            bool ragged = false;
+#pragma unroll
+            for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
+            if (ragged)
+                attn_chunk_step<D, WIN_NB, true>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+            else
+                attn_chunk_step<D, WIN_NB, false>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+        }
+        finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + q0) * ((long)P.h * D) + (long)head * D,
+                            (long)P.h * D, min(32, S - q0));
+    }
 }
 
 // ------------------------------------------------------------------ global kernel
@@ -267,8 +394,7 @@ template <int D>
 size_t global_lds_bytes(int w)
 {
     int ts = w | 1;
-    return (size_t)GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)D * (GLB_TILE + 4) * 2 + (size_t)4 * 32 * 2 * ts * 4 +
-           (size_t)GLB_TILE * 4;
+    return (size_t)2 * GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)4 * wave_scratch_bytes<D>(ts) + (size_t)GLB_TILE * 4;
 }
 
 template <int D>
@@ -279,11 +405,12 @@ attn_global_kernel(AttnParams P, int T)
     constexpr int LOADS = GLB_TILE * C::CH / 256;       // 16-byte chunks per thread per operand
     static_assert(GLB_TILE * C::CH % 256 == 0, "tile chunks must divide over the workgroup");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int vstr = GLB_TILE + 4, ts = P.w | 1;
+    const int ts = P.w | 1;
     bf16 *Ks = reinterpret_cast<bf16 *>(smem);
-    bf16 *Vt = Ks + GLB_TILE * C::KSTR;
-    float *Tb = reinterpret_cast<float *>(Vt + D * vstr);
-    uint32_t *krc = reinterpret_cast<uint32_t *>(Tb + 4 * 32 * 2 * ts);
+    bf16 *Vs = Ks + GLB_TILE * C::KSTR;
+    unsigned char *Tb = reinterpret_cast<unsigned char *>(Vs + GLB_TILE * C::KSTR);
+    const int wsb = wave_scratch_bytes<D>(ts);
+    uint32_t *krc = reinterpret_cast<uint32_t *>(Tb + 4 * wsb);
 
     const int qt = blockIdx.x % T, gh = blockIdx.x / T;
     const int grp = gh / P.h, head = gh % P.h;
@@ -296,16 +423,7 @@ attn_global_kernel(AttnParams P, int T)
     bf16x8 qf[C::KS];
     load_q_frags<D>(qf, P.q + base + (long)qclamp * P.row_stride);
     const uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
-    float *th = Tb + wave * 32 * 2 * ts, *tw = th + 32 * ts;
-    build_bias_rows<D>(qf, P.rel_h, P.rel_w, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), th, tw, ts);
-
-    WaveState<D> st;
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
-    st.m = -INFINITY;
-    st.l = 0.f;
+    float *tq = reinterpret_cast<float *>(Tb + wave * wsb);
 
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
     u32x4 rk[LOADS], rv[LOADS];
@@ -321,7 +439,7 @@ attn_global_kernel(AttnParams P, int T)
             rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8);    \
             rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8);    \
         }                                                                                               \
-        if (tid < GLB_TILE) rrc = key_row_col(P.sigma, key0_ + tid, S, P.w);                            \
+        if (tid < GLB_TILE) rrc = key_bias_offsets(P.sigma, key0_ + tid, S, P.w, ts);                   \
     }
 #define ATTN_STORE_TILE()                                                                               \
     {                                                                                                   \
@@ -329,27 +447,33 @@ attn_global_kernel(AttnParams P, int T)
         {                                                                                               \
             int id = tid + i * 256, key = id / C::CH, c = id % C::CH;                                   \
             *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = rk[i];                             \
-            const bf16x8 ve = __builtin_bit_cast(bf16x8, rv[i]);                                        \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * vstr + key] = ve[e];         \
+            *reinterpret_cast<u32x4 *>(Vs + key * C::KSTR + c * 8) = rv[i];                             \
         }                                                                                               \
         if (tid < GLB_TILE) krc[tid] = rrc;                                                             \
     }
 
-    ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt)
+    ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt)          // in flight while the bias rows are formed
+    build_bias_rows<D>(qf, P.rel_h, P.rel_w, D, false, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+
+    WaveState<D> st;
+    init_state<D>(st);
     for (int a = 0; a < nact; ++a) {
         const int kt = a < P.n_pre ? a : qt;
-        __syncthreads();                       // every wave is done with the previous tile
+        LDS_BARRIER();                         // every wave is done with the previous tile
         ATTN_STORE_TILE()
-        __syncthreads();
+        LDS_BARRIER();
         if (a + 1 < nact) ATTN_LOAD_TILE(a + 1 < P.n_pre ? a + 1 : qt)
-#pragma unroll 1
-        for (int kb = 0; kb < GLB_TILE / 32; ++kb) {
-            if (kt * GLB_TILE + kb * 32 >= S) break;     // wholly past the end
-            attn_block_step<D>(st, qf, Ks + kb * 32 * C::KSTR, Vt, vstr, kb * 32, krc + kb * 32,
-                               kt * GLB_TILE + kb * 32, S, P.scale_log2e, th + l32 * ts, tw + l32 * ts);
-        }
+        const int blk[4] = { 0, 1, 2, 3 };
+        const int key0[4] = { kt * GLB_TILE, kt * GLB_TILE + 32, kt * GLB_TILE + 64, kt * GLB_TILE + 96 };
+        const int nb = min(4, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
+        if (kt * GLB_TILE + GLB_TILE > S)
+            attn_chunk_step<D, 4, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+        else
+            attn_chunk_step<D, 4, false>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
     }
-    finish_and_store<D>(st, P.out + ((long)grp * S + qclamp) * ((long)P.h * D) + (long)head * D, qpos < S);
+    const int qw0 = qt * GLB_TILE + wave * 32;
+    finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + qw0) * ((long)P.h * D) + (long)head * D,
+                        (long)P.h * D, min(32, S - qw0));
 }
 
 template <int D>
@@ -363,7 +487,14 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
         if (lds > 64 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return SSAM_EHIP;
-        hipLaunchKernelGGL(kern, dim3(groups * P.h), dim3(nqb * 64), lds, st, P);
+        if (ssam_div_up((long)nqb * 32 * AttnCfg<D>::CH, nqb * 64) > WIN_MAX_LOADS) return SSAM_EUNSUPPORTED;
+        int n_problems = groups * P.h;
+        // persistent workgroups: as many as fit on the 256 CUs at once for this LDS footprint
+        int per_cu = (int)((160 * 1024) / lds);
+        if (per_cu < 1) per_cu = 1;
+        if (per_cu > 4) per_cu = 4;
+        int grid = n_problems < 256 * per_cu ? n_problems : 256 * per_cu;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(nqb * 64), lds, st, P, n_problems);
     } else {
         int T = ssam_div_up(P.S, GLB_TILE);
         size_t lds = global_lds_bytes<D>(P.w);
