@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain row copy of known size (identity ssam_permute over the input batch), "
+                         "the reference kernel that scales the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -86,6 +89,20 @@ def device_weights(torch, seed, shape, g, dev):
             "w2": n(shape.D, shape.Dm, dtype=bf), "b2": n(shape.D),
         })
     return blocks
+
+
+def profile_traffic(model):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None when no summary exists."""
+    path = os.path.join(ROOT, "profiles", f"gemm_qkv_{model}_b8_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def encoder_flops(shape, g, B, r, rho, K):
@@ -180,6 +197,13 @@ def main():
         dt = time.perf_counter() - t0
         return dt, evs
 
+    if args.calibrate_copy:
+        ident = torch.arange(n, dtype=torch.int32, device=dev)
+        ycopy = torch.empty_like(x0)
+        for _ in range(3):
+            B.ssam_permute(x0, ident, ycopy)           # reads and writes B*N*D*2 bytes each
+        torch.cuda.synchronize()
+
     dt, evs = timed(cfg_l, cfg_g, keep, args.steps, args.warmup, True)
     ms_per_step = dt / args.steps * 1e3
     images_per_s = Bn * args.steps / dt
@@ -196,7 +220,7 @@ def main():
     roofline = {
         "kernel": "gemm_bf16_nt_kernel (qkv contraction, bias epilogue)",
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": profile_traffic(shape.name),
         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": shape.depth,
         "flops_per_launch": avg_flops,
         "shape": f"M={Bn * rows_local} (local) / {Bn * n} (global), N={3 * shape.D}, K={shape.D}",

@@ -75,5 +75,20 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// exact (erf) GELU
-__device__ __forceinline__ float gelu_erf(float t) { return 0.5f * t * (1.0f + erff(t * 0.70710678118654752440f)); }
+// erf GELU, 0.5 t (1 + erf(t / sqrt 2)).  erf by the rational approximation 7.1.26 of Abramowitz & Stegun,
+// erf(x) = 1 - (a1 u + ... + a5 u^5) exp(-x^2), u = 1 / (1 + p x) for x >= 0, odd in x; absolute error below
+// 1.5e-7, far under the bf16 rounding of the stored activation.  One reciprocal and one exp2 per element.
+__device__ __forceinline__ float gelu_erf(float t)
+{
+    const float x = fabsf(t) * 0.70710678118654752440f;
+    const float u = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float poly = fmaf(1.061405429f, u, -1.453152027f);
+    poly = fmaf(poly, u, 1.421413741f);
+    poly = fmaf(poly, u, -0.284496736f);
+    poly = fmaf(poly, u, 0.254829592f);
+    poly *= u;
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
+    const float erf_abs = fmaf(-poly, e, 1.0f);                 // erf(|t| / sqrt 2)
+    const float erf_signed = copysignf(erf_abs, t);
+    return 0.5f * t * (1.0f + erf_signed);
+}
