@@ -122,10 +122,30 @@ int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M,
                 int dst_rows_per_batch, void *stream);
 
 /* The same with the workgroup tile forced (tuning and tests): tile = 0 picks
- * automatically, 1 = 256x256 (needs N % 256 == 0), 2 = 256x128, 3 = 128x128. */
+ * automatically, 1 = 256x256 (needs N % 256 == 0), 2 = 256x128, 3 = 128x128.
+ * With any tile, when the tiles fill at least one round of workgroups and the
+ * left-over is under half a round, the left-over tiles run as a second launch
+ * of half- or quarter-size tiles; results do not depend on the tile choice
+ * beyond fp32 summation order (which is the same: K is never split). */
 int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
                       int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
                       int dst_rows_per_batch, int tile, void *stream);
+
+/* The general form: A, W and C with their own row strides lda >= K, ldw >= K,
+ * ldc >= N in elements (multiples of 8, else SSAM_EINVAL; for the scatter
+ * epilogue ldc is the row stride of the destination), and an optional device
+ * workspace (NULL/0 for none; 16-byte aligned; ssam_linear_workspace_bytes()
+ * is always enough, smaller is allowed).  With a workspace, a left-over launch
+ * of few tiles over a long K (K >= 2048) is cut along K as well: partial fp32
+ * tiles go to the workspace and are added in a fixed order, so results are
+ * reproducible; they can differ from the no-workspace result in the last bit
+ * of the fp32 sum.  The workspace is scratch: contents undefined afterwards,
+ * concurrent calls need separate workspaces. */
+size_t ssam_linear_workspace_bytes(void);
+int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, const float *bias, void *C, int ldc,
+                   int M, int N, int K, int epilogue, const int32_t *row_map, int rows_per_batch,
+                   int map_batch_stride, int dst_rows_per_batch, int tile,
+                   void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Stripe-Sort attention (App. A.1, Alg. 1)                                  */

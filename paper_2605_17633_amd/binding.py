@@ -47,7 +47,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.ssam_status_string.restype = C.c_char_p
         for n in ("ssam_score_tokens_workspace_bytes", "ssam_routed_mlp_workspace_bytes",
-                  "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes"):
+                  "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes", "ssam_linear_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         _lib = L
     return _lib
@@ -163,6 +163,34 @@ def ssam_linear(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows_pe
         _bf(A, "A"), _bf(W, "W"), _f32(bias, "bias"), _bf(C_out, "C"), C.c_int(M), C.c_int(N), C.c_int(K),
         C.c_int(epilogue), _i32(row_map, "row_map"), C.c_int(rows_per_batch), C.c_int(map_batch_stride),
         C.c_int(dst_rows_per_batch), C.c_int(tile), _stream()))
+    return C_out
+
+
+def ssam_linear_workspace_bytes():
+    return int(lib().ssam_linear_workspace_bytes())
+
+
+def _rows(t, dtype, name):
+    """Pointer and row stride of a 2-D device tensor whose rows are contiguous (a column slice is fine)."""
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == 2 and t.stride(1) == 1):
+        raise TypeError(f"{name}: expected a 2-D device tensor of {dtype} with contiguous rows")
+    return C.c_void_p(t.data_ptr()), C.c_int(t.stride(0))
+
+
+def ssam_linear_ld(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows_per_batch=1, map_batch_stride=0,
+                   dst_rows_per_batch=1, tile=0, workspace=None):
+    """ssam_linear on operands with their own row strides, with an optional scratch workspace (uint8)."""
+    M, K = A.shape
+    N = W.shape[0]
+    assert W.shape[1] == K
+    if C_out is None:
+        C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    (pa, lda), (pw, ldw), (pc, ldc) = _rows(A, torch.bfloat16, "A"), _rows(W, torch.bfloat16, "W"), _rows(C_out, torch.bfloat16, "C")
+    _check("ssam_linear_ld", lib().ssam_linear_ld(
+        pa, lda, pw, ldw, _f32(bias, "bias"), pc, ldc, C.c_int(M), C.c_int(N), C.c_int(K),
+        C.c_int(epilogue), _i32(row_map, "row_map"), C.c_int(rows_per_batch), C.c_int(map_batch_stride),
+        C.c_int(dst_rows_per_batch), C.c_int(tile), _dev(workspace, torch.uint8, "workspace"),
+        C.c_size_t(0 if workspace is None else workspace.numel()), _stream()))
     return C_out
 
 

@@ -6,7 +6,8 @@
 #include "gemm_kernel.h"
 
 int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
-                     int epilogue, const GemmRowMap &rm, int tile, hipStream_t st);
+                     const GemmLd &ld, int epilogue, const GemmRowMap &rm, int tile,
+                     void *split_ws, size_t split_ws_bytes, hipStream_t st);
 
 namespace {
 
@@ -30,10 +31,13 @@ bool block_geom(const ssam_block_cfg *c, BlockGeom &g)
     return true;
 }
 
-size_t mlp_ws_bytes(int B, int K, int D, int Dm)
+// gathered LN2 rows, hidden activations, then the K-split scratch of the fc2 contraction
+size_t mlp_core_bytes(int B, int K, int D, int Dm)
 {
     return align256((size_t)B * K * D * 2) + align256((size_t)B * K * Dm * 2);
 }
+
+size_t mlp_ws_bytes(int B, int K, int D, int Dm) { return mlp_core_bytes(B, K, D, Dm) + GEMM_SPLIT_WS_BYTES; }
 
 }  // namespace
 
@@ -56,14 +60,16 @@ extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln
     unsigned char *ws = (unsigned char *)workspace;
     void *a2 = ws;
     void *hid = ws + align256((size_t)B * K * D * 2);
+    void *split = ws + mlp_core_bytes(B, K, D, Dm);
     hipStream_t st = (hipStream_t)stream;
     int rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
-    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, SSAM_EPI_BIAS_GELU, none, 0, st);
+    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, SSAM_EPI_BIAS_GELU, none, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     GemmRowMap scatter = { keep_idx, K, K, N };
-    return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0, st);
+    return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, GemmLd{ Dm, Dm, D }, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0,
+                            split, GEMM_SPLIT_WS_BYTES, st);
 }
 
 extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
@@ -97,7 +103,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, SSAM_EPI_BIAS, none, 0, st);
+    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, SSAM_EPI_BIAS, none, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
@@ -106,7 +112,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
                                1.0f / sqrtf((float)g.d), stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap back = { gather_table, g.Nout, 0, g.N };
-    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, st);
+    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     return ssam_routed_mlp(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2,
                            B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);

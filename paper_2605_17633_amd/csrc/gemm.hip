@@ -3,52 +3,114 @@
 
 namespace {
 
-template <int BM, int BN, int EPI>
-int launch_gemm(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
-                const GemmRowMap &rm, hipStream_t st)
+struct SplitWs { void *ptr; size_t bytes; };
+
+// How a launch of `total` large tiles over `slots` concurrent workgroups is cut: `rem` left-over large
+// tiles go to a second launch of `subs` smaller tiles each (0: none, when the tiles do not fill one
+// round, fill the last one exactly, or fill more than half of it), and that launch also cuts K into
+// `parts` ranges (1: no) when a workspace is there, K is long and the left-over is small.
+struct TailPlan { int rem, parts; };
+
+TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes, const SplitWs &ws)
 {
+    TailPlan p = { total % slots, 1 };
+    if (total < slots || p.rem > slots / 2) p.rem = 0;
+    if (p.rem == 0) return p;
+    const int n_sub = p.rem * subs;
+    int parts = nk / 8;
+    if (parts > 256 / n_sub) parts = 256 / n_sub;
+    if (ws.ptr && parts >= 4 && (size_t)n_sub * parts * sub_tile_bytes <= ws.bytes) p.parts = parts;
+    return p;
+}
+
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N>
+int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
+                 const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm, const GemmSplit &sp, hipStream_t st)
+{
+    if (tr.tile_count <= 0) return SSAM_OK;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI>;
+    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N>;
     // more than 64 KiB of LDS per workgroup needs the per-kernel opt-in (idempotent, host-side only)
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SSAM_EHIP;
-    int tiles_m = ssam_div_up(M, BM), tiles_n = N / BN;
-    int per_xcd = ssam_div_up((long)tiles_m * tiles_n, 8);
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(GEMM_THREADS), lds, st, A, W, bias, C, M, N, K, tiles_m, tiles_n, rm);
+    int per_xcd = ssam_div_up((long)tr.tile_count * SUB_M * SUB_N * sp.parts, 8);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(GEMM_THREADS), lds, st, A, W, bias, C, M, N, K, ld, tr, rm, sp);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }
 
-template <int BM, int BN>
-int launch_gemm_epi(int epi, const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
-                    const GemmRowMap &rm, hipStream_t st)
+// Whole rounds of BM x BN tiles, then the left-over tiles (when they would fill less than half a round)
+// as TM x TN tiles, BM = SUB_M*TM, BN = SUB_N*TN.  slots = workgroups the chip runs at once with the large
+// tile.  With a workspace, a long K and few left-over tiles, the left-over launch also cuts K (see the kernel).
+template <int BM, int BN, int TM, int TN, int EPI>
+int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
+                 const GemmLd &ld, int slots, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
-    switch (epi) {
-    case SSAM_EPI_BIAS: return launch_gemm<BM, BN, SSAM_EPI_BIAS>(A, W, bias, C, M, N, K, rm, st);
-    case SSAM_EPI_BIAS_GELU: return launch_gemm<BM, BN, SSAM_EPI_BIAS_GELU>(A, W, bias, C, M, N, K, rm, st);
-    case SSAM_EPI_BIAS_SCATTER_ADD: return launch_gemm<BM, BN, SSAM_EPI_BIAS_SCATTER_ADD>(A, W, bias, C, M, N, K, rm, st);
+    constexpr int SUB_M = BM / TM, SUB_N = BN / TN;
+    const GemmSplit whole = { nullptr, 1 };
+    GemmTileRange tr = { ssam_div_up(M, BM), N / BN, 0, 0 };
+    const int total = tr.tiles_m * tr.tiles_n;
+    const int nk = K / GEMM_BK;
+    const TailPlan plan = plan_tail(total, slots, nk, SUB_M * SUB_N, (size_t)TM * TN * sizeof(float), ws);
+    const int rem = plan.rem, parts = plan.parts;
+    tr.tile_count = total - rem;
+    int rc = launch_range<BM, BN, EPI, 1, 1>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    if (rc != SSAM_OK || rem == 0) return rc;
+    tr.tile_begin = total - rem;
+    tr.tile_count = rem;
+    const int n_sub = rem * SUB_M * SUB_N;
+    if (parts > 1) {
+        const GemmSplit sp = { (float *)ws.ptr, parts };
+        rc = launch_range<TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N>(A, W, bias, C, M, N, K, ld, tr, rm, sp, st);
+        if (rc != SSAM_OK) return rc;
+        constexpr int RPB = 256 / (TN / 8);
+        hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
+                           (const float *)ws.ptr, parts, bias, C, M, N, ld, tr, rm);
+        SSAM_CHECK_LAUNCH();
+        return SSAM_OK;
+    }
+    return launch_range<TM, TN, EPI, SUB_M, SUB_N>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+}
+
+template <int EPI>
+int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
+                const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
+{
+    switch (tile) {
+    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
     default: return SSAM_EINVAL;
     }
 }
 
-// Pick the tile by a small cost model: relative throughput of a full machine of such tiles
-// (measured on MI355X on the ViT-H layer shapes: the 256x256 tile reads least LDS per flop; the
-// 128x128 tile runs two workgroups per CU) times the fill of the last round of workgroups.
-int pick_tile(int M, int N)
+// Pick the tile by a time model in microseconds, fitted on MI355X to the ViT-H layer shapes: a round of
+// workgroups costs nk * t_slab + t_epi (the 256x256 tile reads least LDS per flop but runs one workgroup
+// per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one workgroup's
+// epilogue behind the other's main loop); the
+// left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
+int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
 {
-    struct Cand { int id, bm, bn, slots; double eff; };
-    const Cand cands[3] = { { 1, 256, 256, 256, 1.00 }, { 2, 256, 128, 256, 0.78 }, { 3, 128, 128, 512, 0.80 } };
+    struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[3]; };
+    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.80, { 8.0, 17.8, 18.7 } },
+                            { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5 } },
+                            { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8 } } };
+    const int nk = K / GEMM_BK;
     int best = 3;
-    double best_score = -1.0;
+    double best_time = 1e30;
     for (const Cand &c : cands) {
         if (N % c.bn != 0) continue;
-        long tiles = (long)ssam_div_up(M, c.bm) * (N / c.bn);
-        long rounds = (tiles + c.slots - 1) / c.slots;
-        double fill = (double)tiles / (double)(rounds * c.slots);
-        double ragged = (double)M / ((double)ssam_div_up(M, c.bm) * c.bm);
-        double score = c.eff * fill * ragged;
-        if (score > best_score) { best_score = score; best = c.id; }
+        const int subs = (c.bm / c.tm) * (c.bn / c.tn);
+        const int total = ssam_div_up(M, c.bm) * (N / c.bn);
+        const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
+        const double round = nk * c.t_slab + c.t_epi[epilogue];
+        double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
+        if (plan.rem != 0) {
+            const int n_sub = plan.rem * subs;
+            t += plan.parts > 1 ? ssam_div_up(nk, plan.parts) * 0.9 + 12.0 : (nk * 0.75 + 5.0) * (1.0 + n_sub / 1024.0);
+        }
+        if (t < best_time) { best_time = t; best = c.id; }
     }
     return best;
 }
@@ -56,25 +118,32 @@ int pick_tile(int M, int N)
 }  // namespace
 
 int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
-                     int epilogue, const GemmRowMap &rm, int tile, hipStream_t st)
+                     const GemmLd &ld, int epilogue, const GemmRowMap &rm, int tile,
+                     void *split_ws, size_t split_ws_bytes, hipStream_t st)
 {
+    const SplitWs ws = { split_ws, split_ws_bytes };
     const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
     bf16 *c = (bf16 *)C;
-    if (tile == 0) tile = pick_tile(M, N);
-    switch (tile) {
-    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_gemm_epi<256, 256>(epilogue, a, w, bias, c, M, N, K, rm, st);
-    case 2: return launch_gemm_epi<256, 128>(epilogue, a, w, bias, c, M, N, K, rm, st);
-    case 3: return launch_gemm_epi<128, 128>(epilogue, a, w, bias, c, M, N, K, rm, st);
+    if (tile == 0) tile = pick_tile(M, N, K, epilogue, ws);
+    switch (epilogue) {
+    case SSAM_EPI_BIAS: return launch_tile<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+    case SSAM_EPI_BIAS_GELU: return launch_tile<SSAM_EPI_BIAS_GELU>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+    case SSAM_EPI_BIAS_SCATTER_ADD: return launch_tile<SSAM_EPI_BIAS_SCATTER_ADD>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
     default: return SSAM_EINVAL;
     }
 }
 
-extern "C" int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
-                                 int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
-                                 int dst_rows_per_batch, int tile, void *stream)
+extern "C" size_t ssam_linear_workspace_bytes(void) { return GEMM_SPLIT_WS_BYTES; }
+
+extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, const float *bias, void *C, int ldc,
+                              int M, int N, int K, int epilogue, const int32_t *row_map, int rows_per_batch,
+                              int map_batch_stride, int dst_rows_per_batch, int tile,
+                              void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!A || !W || !bias || !C || M <= 0 || N <= 0 || K <= 0) return SSAM_EINVAL;
     if (!ssam_aligned16(A) || !ssam_aligned16(W) || !ssam_aligned16(bias) || !ssam_aligned16(C)) return SSAM_EINVAL;
+    if (lda < K || ldw < K || ldc < N || lda % 8 || ldw % 8 || ldc % 8) return SSAM_EINVAL;
+    if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
     if (N % 128 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
     if (tile < 0 || tile > 3) return SSAM_EINVAL;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
@@ -84,13 +153,23 @@ extern "C" int ssam_linear_tiled(const void *A, const void *W, const float *bias
     } else if (epilogue != SSAM_EPI_BIAS && epilogue != SSAM_EPI_BIAS_GELU) {
         return SSAM_EINVAL;
     }
-    return ssam_linear_impl(A, W, bias, C, M, N, K, epilogue, rm, tile, (hipStream_t)stream);
+    GemmLd ld = { lda, ldw, ldc };
+    return ssam_linear_impl(A, W, bias, C, M, N, K, ld, epilogue, rm, tile, workspace, workspace ? workspace_bytes : 0,
+                            (hipStream_t)stream);
+}
+
+extern "C" int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
+                                 int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
+                                 int dst_rows_per_batch, int tile, void *stream)
+{
+    return ssam_linear_ld(A, K, W, K, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
+                          dst_rows_per_batch, tile, nullptr, 0, stream);
 }
 
 extern "C" int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
                            int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
                            int dst_rows_per_batch, void *stream)
 {
-    return ssam_linear_tiled(A, W, bias, C, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
-                             dst_rows_per_batch, 0, stream);
+    return ssam_linear_ld(A, K, W, K, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
+                          dst_rows_per_batch, 0, nullptr, 0, stream);
 }

@@ -15,6 +15,14 @@
 // consecutive columns and issues 16-byte global accesses.
 // Tiles are dealt so that each XCD (its own L2) works on a contiguous run of tiles, ordered in
 // bands of 8 tile rows: workgroups that run together share A and W panels.
+// A launch covers a range [tile_begin, tile_begin + tile_count) of "parent" tiles of (BM*SUB_M) x (BN*SUB_N)
+// in that order, each cut into SUB_M x SUB_N tiles of this kernel: the dispatcher runs whole rounds of
+// large tiles and hands the few left-over large tiles to a second launch of smaller ones, so that the
+// last round of workgroups is short instead of a full large-tile time.  When K is long those few
+// workgroups would each walk all of K alone, bound by the latency of one slab after the other, so the
+// left-over launch can also cut K into `parts` ranges (epilogue GEMM_EPI_PARTIAL): every workgroup
+// leaves its fp32 tile in a workspace slot of its own and gemm_tail_reduce_kernel adds the slots in a
+// fixed order and applies the real epilogue (the result does not depend on timing).
 #pragma once
 
 #include "common.h"
@@ -33,7 +41,7 @@ template <int BM, int BN>
 constexpr size_t gemm_lds_bytes()
 {
     size_t pipe = (size_t)2 * (BM + BN) * GEMM_BK * sizeof(bf16);
-    size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);
+    size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float) + BM * sizeof(int);   // staging + scatter rows
     return pipe > epi ? pipe : epi;
 }
 
@@ -42,14 +50,42 @@ __device__ __forceinline__ int gemm_swz(int row, int c) { return row * GEMM_BK +
 
 #define GEMM_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
-template <int BM, int BN, int EPI>
+struct GemmLd { int a, w, c; };   // row strides of A, W and C in elements (multiples of 8)
+
+struct GemmTileRange {
+    int tiles_m, tiles_n;     // parent tile grid
+    int tile_begin, tile_count;   // parent tiles of this launch, in band order
+};
+
+constexpr int GEMM_EPI_PARTIAL = 3;   // internal: store the fp32 tile of one K range, no bias
+constexpr int GEMM_GROUP_M = 8;
+constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)16 << 20;   // workspace that lets the left-over launch cut K
+
+struct GemmSplit {
+    float *partial;           // [tile_count*SUB_M*SUB_N][parts][BM][BN] fp32, NULL unless GEMM_EPI_PARTIAL
+    int parts;                // K ranges per tile (1 otherwise); parts <= K/64
+};
+
+// origin of sub-tile `sub` of parent tile t (band order over the parent grid)
+__device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t, int sub, int sub_m, int sub_n,
+                                                 int bm, int bn, int &m0, int &n0)
+{
+    const int band = GEMM_GROUP_M * tr.tiles_n;
+    const int first_m = (t / band) * GEMM_GROUP_M;
+    const int band_rows = min(GEMM_GROUP_M, tr.tiles_m - first_m);
+    const int tm = first_m + (t % band) % band_rows;
+    const int tn = (t % band) / band_rows;
+    m0 = (tm * sub_m + sub / sub_n) * bm;
+    n0 = (tn * sub_n + sub % sub_n) * bn;
+}
+
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1>
 __global__ void __launch_bounds__(GEMM_THREADS)
 gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
-                    bf16 *C, int M, int N, int K, int tiles_m, int tiles_n, GemmRowMap rm)
+                    bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
 {
     constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
     constexpr int A_LOADS = BM * 8 / GEMM_THREADS, B_LOADS = BN * 8 / GEMM_THREADS;
-    constexpr int GROUP_M = 8;
     constexpr int NM = MT * NT, NR = MT + NT, NL = A_LOADS + B_LOADS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16 *As = reinterpret_cast<bf16 *>(smem);                 // [2][BM*64]
@@ -57,21 +93,22 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 
     // ---- tile assignment: workgroups are dealt round-robin to the 8 XCDs; XCD x takes the tiles
     // x*per_xcd .. (x+1)*per_xcd-1 of the band order
-    const int total = tiles_m * tiles_n;
+    constexpr int SUBS = SUB_M * SUB_N;
+    const int parts = EPI == GEMM_EPI_PARTIAL ? sp.parts : 1;
+    const int total = tr.tile_count * SUBS * parts;
     const int per_xcd = (total + 7) / 8;
-    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (t >= total) return;
-    const int band = GROUP_M * tiles_n;
-    const int first_m = (t / band) * GROUP_M;
-    const int band_rows = min(GROUP_M, tiles_m - first_m);
-    const int tm = first_m + (t % band) % band_rows;
-    const int tn = (t % band) / band_rows;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int tl = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tl >= total) return;
+    const int kpart = tl % parts, slot = tl / parts;            // slot: sub-tile index within this launch
+    int m0, n0;
+    gemm_tile_origin(tr, tr.tile_begin + slot / SUBS, slot % SUBS, SUB_M, SUB_N, BM, BN, m0, n0);
+    if (m0 >= M) return;                        // a sub-tile wholly below the last row
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
     const int l32 = lane & 31, half = lane >> 5;
     const int nk = K / GEMM_BK;
+    const int kb = (int)((long)nk * kpart / parts), ke = (int)((long)nk * (kpart + 1) / parts);   // this workgroup's slabs
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -89,8 +126,8 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     const bf16 *ga[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i)          // rows past M repeat the last row; their results are never stored
-        ga[i] = A + (long)min(m0 + r0 + 32 * i, M - 1) * K + c0 * 8;
-    const bf16 *gb = W + (long)(n0 + r0) * K + c0 * 8;
+        ga[i] = A + (long)min(m0 + r0 + 32 * i, M - 1) * ld.a + c0 * 8;
+    const bf16 *gb = W + (long)(n0 + r0) * ld.w + c0 * 8;
     const int lst = gemm_swz(r0, c0);          // + i*32*64: rows 32 apart share the swizzle term
     const int fa0 = (wm + l32) * GEMM_BK, fb0 = (wn + l32) * GEMM_BK;
     const int sw = (l32 >> 1) & 7;
@@ -100,7 +137,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
             ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + (kt_) * GEMM_BK);                        \
         _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
-            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * 32 * K + (kt_) * GEMM_BK);        \
+            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * 32 * ld.w + (kt_) * GEMM_BK);        \
     }
 #define GEMM_STORE_LDS(buf_)                                                                          \
     {                                                                                                 \
@@ -127,11 +164,11 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], bfr[slot_][j], acc[i][j], 0, 0, 0); \
     }
 
-    GEMM_LOAD_GLOBAL(0)
+    GEMM_LOAD_GLOBAL(kb)
     GEMM_STORE_LDS(0)
     LDS_BARRIER();
     int buf = 0;
-    for (int kt = 0; kt < nk - 1; ++kt, buf ^= 1) {
+    for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
         GEMM_LOAD_FRAGS(buf, 0, 0)
         GEMM_LOAD_GLOBAL(kt + 1)
         GEMM_LOAD_FRAGS(buf, 1, 1)
@@ -176,15 +213,43 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     const int cl = lane % LPR, rl = lane / LPR;
     const int ncol = n0 + wn + cl * 8;
     float bv[8];
-    {
+    if (EPI == GEMM_EPI_PARTIAL) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+    } else {
         const float4 *b4 = reinterpret_cast<const float4 *>(bias + ncol);
         float4 x0 = b4[0], x1 = b4[1];
         bv[0] = x0.x; bv[1] = x0.y; bv[2] = x0.z; bv[3] = x0.w;
         bv[4] = x1.x; bv[5] = x1.y; bv[6] = x1.z; bv[7] = x1.w;
     }
+    // The scatter epilogue is a read-modify-write of rows of the residual stream.  Its destination rows
+    // are looked up once per tile (one row per thread, parked in LDS behind the staging regions) and the
+    // old values of a whole 32-row slice are requested before the slice is staged, so that the slice pays
+    // one memory round trip instead of one per pass.
+    constexpr int PASSES = 32 / RPP;
+    int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + 4 * 32 * EPS);   // [BM], -1 = skip
+    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+        int mine = -1;
+        if (tid < BM && m0 + tid < M) {
+            int m = m0 + tid, b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
+            int idx = rm.map[(long)b * rm.map_batch_stride + p];
+            if (idx >= 0 && idx < rm.dst_rows_per_batch) mine = b * rm.dst_rows_per_batch + idx;
+        }
+        __syncthreads();                        // every wave is done with the pipeline buffers
+        if (tid < BM) dst_row[tid] = mine;
+    }
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         __syncthreads();
+        uint4 old[PASSES];
+        int drow[PASSES];
+        if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) {
+                drow[pass] = dst_row[wm + i * 32 + pass * RPP + rl];
+                if (drow[pass] >= 0) old[pass] = *reinterpret_cast<const uint4 *>(C + (long)drow[pass] * ld.c + ncol);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -192,12 +257,18 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 stage[(8 * (r >> 2) + 4 * half + (r & 3)) * EPS + j * 32 + l32] = acc[i][j][r];
         __syncthreads();
 #pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
+        for (int pass = 0; pass < PASSES; ++pass) {
             const int row = pass * RPP + rl;
             const int m = m0 + wm + i * 32 + row;
             if (m >= M) continue;
             const float4 *s4 = reinterpret_cast<const float4 *>(stage + row * EPS + cl * 8);
             float4 y0 = s4[0], y1 = s4[1];
+            if (EPI == GEMM_EPI_PARTIAL) {
+                float4 *dst = reinterpret_cast<float4 *>(sp.partial + (((long)slot * parts + kpart) * BM + (wm + i * 32 + row)) * BN + wn + cl * 8);
+                dst[0] = y0;
+                dst[1] = y1;
+                continue;
+            }
             float v[8] = { y0.x + bv[0], y0.y + bv[1], y0.z + bv[2], y0.w + bv[3],
                            y1.x + bv[4], y1.y + bv[5], y1.z + bv[6], y1.w + bv[7] };
             if (EPI == SSAM_EPI_BIAS_GELU) {
@@ -205,18 +276,67 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
             }
             if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
-                int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
-                int idx = rm.map[(long)b * rm.map_batch_stride + p];
-                if (idx < 0 || idx >= rm.dst_rows_per_batch) continue;
-                uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)b * rm.dst_rows_per_batch + idx) * N + ncol);
+                if (drow[pass] < 0) continue;
                 float o[8];
-                unpack_bf16x8(*dst, o);
+                unpack_bf16x8(old[pass], o);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] += o[e];
-                *dst = pack_bf16x8(v);
+                *reinterpret_cast<uint4 *>(C + (long)drow[pass] * ld.c + ncol) = pack_bf16x8(v);
             } else {
-                *reinterpret_cast<uint4 *>(C + (long)m * N + ncol) = pack_bf16x8(v);
+                *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);
             }
         }
+    }
+}
+
+// Second half of a K-split left-over launch: adds the `parts` fp32 slots of every sub-tile in slot
+// order, then bias and the epilogue proper.  One thread finishes 8 consecutive columns of a row.
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N>
+__global__ void __launch_bounds__(256)
+gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const float *__restrict__ bias, bf16 *C,
+                        int M, int N, GemmLd ld, GemmTileRange tr, GemmRowMap rm)
+{
+    constexpr int LPR = BN / 8, RPB = 256 / LPR;                  // lanes per row, rows per workgroup
+    constexpr int SUBS = SUB_M * SUB_N;
+    const int slot = blockIdx.x / (BM / RPB);
+    const int row = (blockIdx.x % (BM / RPB)) * RPB + threadIdx.x / LPR;
+    const int col = (threadIdx.x % LPR) * 8;
+    int m0, n0;
+    gemm_tile_origin(tr, tr.tile_begin + slot / SUBS, slot % SUBS, SUB_M, SUB_N, BM, BN, m0, n0);
+    const int m = m0 + row, ncol = n0 + col;
+    if (m >= M) return;
+    float v[8];
+    {
+        const float4 *b4 = reinterpret_cast<const float4 *>(bias + ncol);
+        float4 x0 = b4[0], x1 = b4[1];
+        v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
+        v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+    }
+    float acc[8] = { 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f };
+    const float *src = partial + ((long)slot * parts * BM + row) * BN + col;
+    for (int p = 0; p < parts; ++p) {
+        const float4 *s4 = reinterpret_cast<const float4 *>(src + (long)p * BM * BN);
+        float4 y0 = s4[0], y1 = s4[1];
+        acc[0] += y0.x; acc[1] += y0.y; acc[2] += y0.z; acc[3] += y0.w;
+        acc[4] += y1.x; acc[5] += y1.y; acc[6] += y1.z; acc[7] += y1.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += acc[e];
+    if (EPI == SSAM_EPI_BIAS_GELU) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+    }
+    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+        int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
+        int idx = rm.map[(long)b * rm.map_batch_stride + p];
+        if (idx < 0 || idx >= rm.dst_rows_per_batch) return;
+        uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)b * rm.dst_rows_per_batch + idx) * ld.c + ncol);
+        float o[8];
+        unpack_bf16x8(*dst, o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += o[e];
+        *dst = pack_bf16x8(v);
+    } else {
+        *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);
     }
 }

@@ -144,6 +144,83 @@ def test_linear_bias_and_gelu(tile, M, N, K):
     assert_close(to_np(out), gelu, f"linear gelu tile{tile}", tol=1e-2)
 
 
+@pytest.mark.parametrize("tile,M,N", [(1, 8400, 2048), (2, 8400, 1024), (3, 4200, 2048), (0, 8400, 2048)])
+def test_linear_tail_launch(tile, M, N):
+    """Shapes whose tiles fill one round of workgroups plus a few: whole rounds of the large tile and
+    a second launch of smaller tiles for the rest (ragged last tile row included).  K is never split,
+    so every tile choice gives the same bits."""
+    announce("linear tail launch", tile, M, N)
+    K = 128
+    rng = np.random.default_rng(15)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    Ad, Wd, bd = dev_bf16(A), dev_bf16(W), dev_f32(b)
+    out = B.ssam_linear(Ad, Wd, bd, tile=tile)
+    assert_close(to_np(out), _gemm_ref(A, W, b), f"linear tail tile{tile}", tol=1e-2)
+    other = B.ssam_linear(Ad, Wd, bd, tile=3 if tile != 3 else 2)
+    assert torch.equal(out, other)
+
+
+@pytest.mark.parametrize("tile,M,N,epi", [(1, 8400, 2048, 0), (3, 4200, 2048, 1), (1, 8400, 2048, 2), (2, 8400, 1024, 2)])
+def test_linear_tail_cut_along_k(tile, M, N, epi):
+    """Few left-over tiles and a long K with a workspace: the left-over launch splits K, partial tiles
+    are added in a fixed order.  Bias, GELU and scatter epilogues; reproducible bit for bit."""
+    announce("linear K-split tail", tile, M, N, epi)
+    K = 2048
+    rng = np.random.default_rng(16)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    ws = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    Ad, Wd, bd = dev_bf16(A), dev_bf16(W), dev_f32(b)
+    ref = _gemm_ref(A, W, b)
+    if epi == 2:
+        x = inputs.bf16_round(rng.normal(size=(M + 50, N)).astype(np.float32))
+        rows = np.sort(rng.permutation(M + 50)[:M]).astype(np.int32)
+        outs = []
+        for _ in range(2):
+            xd = dev_bf16(x)
+            B.ssam_linear_ld(Ad, Wd, bd, xd, epilogue=B.EPI_BIAS_SCATTER_ADD, row_map=dev_i32(rows), rows_per_batch=M,
+                             map_batch_stride=0, dst_rows_per_batch=M + 50, tile=tile, workspace=ws)
+            outs.append(xd)
+        assert torch.equal(outs[0], outs[1])
+        got = to_np(outs[0])
+        untouched = np.setdiff1d(np.arange(M + 50), rows)
+        assert np.array_equal(got[untouched].view(np.uint32), x[untouched].view(np.uint32))
+        assert_close(got[rows] - x[rows], ref, f"K-split scatter tile{tile}", stored=got[rows])
+        return
+    out = B.ssam_linear_ld(Ad, Wd, bd, epilogue=epi, tile=tile, workspace=ws)
+    again = B.ssam_linear_ld(Ad, Wd, bd, epilogue=epi, tile=tile, workspace=ws)
+    assert torch.equal(out, again)
+    if epi == 1:
+        ref = torch.nn.functional.gelu(torch.from_numpy(ref)).numpy()
+    assert_close(to_np(out), ref, f"K-split tail tile{tile} epi{epi}", tol=1e-2)
+    plain = B.ssam_linear(Ad, Wd, bd, epilogue=epi, tile=tile)
+    assert_close(to_np(out), to_np(plain).astype(np.float64), "K-split against one-pass tail", tol=1e-2)
+
+
+def test_linear_row_strides():
+    """Operands and result as column slices of wider buffers: strides are honoured, padding untouched."""
+    announce("linear strides")
+    M, N, K = 700, 384, 192
+    rng = np.random.default_rng(17)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    Ab = torch.full((M, K + 64), 7.0, dtype=torch.bfloat16, device=DEV)
+    Wb = torch.full((N, K + 8), 7.0, dtype=torch.bfloat16, device=DEV)
+    Cb = torch.full((M, N + 16), 3.0, dtype=torch.bfloat16, device=DEV)
+    Ab[:, :K] = dev_bf16(A)
+    Wb[:, :K] = dev_bf16(W)
+    B.ssam_linear_ld(Ab[:, :K], Wb[:, :K], dev_f32(b), Cb[:, :N])
+    assert_close(to_np(Cb[:, :N]), _gemm_ref(A, W, b), "linear with row strides", tol=1e-2)
+    assert bool((Cb[:, N:] == 3.0).all())
+    with pytest.raises(B.SsamError) as e:
+        B.ssam_linear_ld(Ab[:, 4:K + 4], Wb[:, :K], dev_f32(b), Cb[:, :N])      # A not 16-byte aligned
+    assert e.value.code == B.EINVAL
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_linear_scatter_add(tile):
     announce("linear scatter", tile)
