@@ -10,8 +10,11 @@ before the timed region.  Prints ONE JSON line.
 Extra legs (run after the timed region, reported inside the same JSON line):
   roofline      the dominant kernel (qkv contraction) timed with HIP events
                 recorded around every launch of it INSIDE the timed region
+  parts         the other entry points of the path timed one by one with HIP
+                events (attention, routed MLP, LN+gather, scores, selection),
+                each against the roofline that bounds it
+  dense, density_0.3   the same kernels at density 1.0 (the "dense GPU block") and 0.3
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
-  dense         the same kernels at density 1.0 (the "dense GPU block")
 """
 from __future__ import annotations
 
@@ -33,13 +36,14 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--model", default="vit_h", choices=["vit_b", "vit_l", "vit_h"])
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--density", type=float, default=0.4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="skip the density 1.0 and 0.3 legs")
+    ap.add_argument("--no-parts", action="store_true", help="skip the per-entry-point timings")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain row copy of known size (identity ssam_permute over the input batch), "
@@ -58,9 +62,13 @@ class Hip:
         assert self.lib.hipEventCreate(C.byref(ev)) == 0
         return ev
 
+    def record(self, ev, stream):
+        assert self.lib.hipEventRecord(ev, C.c_void_p(stream)) == 0
+
     def elapsed_ms(self, a, b):
         ms = C.c_float()
-        rc = self.lib.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b))
+        a, b = (e if isinstance(e, C.c_void_p) else C.c_void_p(e) for e in (a, b))
+        rc = self.lib.hipEventElapsedTime(C.byref(ms), a, b)
         assert rc == 0, rc
         return ms.value
 
@@ -133,6 +141,87 @@ def encoder_flops(shape, g, B, r, rho, K):
     return total * B, qkv_flops
 
 
+def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab, keep, scores, ws_buf, reps=10):
+    """Each remaining entry point of the path on the benchmark's shapes, against its own roofline:
+    algorithmic bytes (rows read + rows written, bf16) over HBM peak, or algorithmic flops over the
+    bf16 MFMA peak.  Outputs are discarded; inputs are the benchmark's tensors."""
+    import math
+    dev = x0.device
+    D, Dm, h, d = shape.D, shape.Dm, shape.heads, shape.D // shape.heads
+    n = g * g
+    nws = -(-g // shape.ws)
+    nW, S = nws * nws, shape.ws ** 2
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = hip.event(), hip.event()
+
+    def run(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        hip.record(e0, stream)
+        for _ in range(reps):
+            fn()
+        hip.record(e1, stream)
+        torch.cuda.synchronize()
+        return hip.elapsed_ms(e0, e1) / reps
+
+    def hbm(ms, nbytes):
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"us": round(ms * 1e3, 1), "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes": int(nbytes)}
+
+    def mfma(ms, flops, extra=None):
+        tf = flops / (ms * 1e-3) / 1e12
+        o = {"us": round(ms * 1e3, 1), "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+             "frac": round(tf / PEAK_BF16_TFLOPS, 4), "flops": float(flops)}
+        if extra:
+            o.update(extra)
+        return o
+
+    def tiles(Sx, Bm):
+        T = -(-Sx // Bm)
+        n_pre = min(T, int(math.floor(r * T + 1e-6)))
+        return n_pre * T + (T - n_pre)
+
+    parts = {}
+    w0 = wts[0]
+    wg_ = wts[shape.global_blocks[0]]
+    bf = torch.bfloat16
+    # LN1 + gather into window-major scan order, and LN2 + gather of the keep-set
+    u = torch.empty((Bn, nW * S, D), dtype=bf, device=dev)
+    ms = run(lambda: B.ssam_ln_gather(x0, wtab, 0, w0["ln1_g"], w0["ln1_b"], 1e-6, nW * S, y=u))
+    parts["ln1_gather_windows"] = hbm(ms, 2.0 * Bn * (n + nW * S) * D)
+    a2 = torch.empty((Bn, K, D), dtype=bf, device=dev)
+    ms = run(lambda: B.ssam_ln_gather(x0, keep, K, w0["ln2_g"], w0["ln2_b"], 1e-6, K, y=a2))
+    parts["ln2_gather_keep"] = hbm(ms, 2.0 * Bn * 2 * K * D)
+    # windowed and global Stripe-Sort attention on a packed qkv tensor
+    qkv = (torch.randn((Bn * nW, S, 3, h, d), device=dev) * 0.7).to(bf)
+    o = torch.empty((Bn * nW, S, D), dtype=bf, device=dev)
+    ms = run(lambda: B.ssam_sparse_attention(qkv, w0["rel_h"], w0["rel_w"], wsig, shape.ws, 32, r, out=o))
+    win = hbm(ms, 2.0 * Bn * nW * S * 4 * D)
+    fl = 4.0 * 32 * 32 * d * tiles(S, 32) * h * Bn * nW
+    win["mfma_tflops"] = round(fl / (ms * 1e-3) / 1e12, 1)
+    parts["attention_windows"] = win
+    del qkv, o
+    qkv = (torch.randn((Bn, n, 3, h, d), device=dev) * 0.7).to(bf)
+    o = torch.empty((Bn, n, D), dtype=bf, device=dev)
+    ms = run(lambda: B.ssam_sparse_attention(qkv, wg_["rel_h"], wg_["rel_w"], gtab, g, 128, r, out=o))
+    parts["attention_global"] = mfma(ms, 4.0 * 128 * 128 * d * tiles(n, 128) * h * Bn,
+                                     {"hbm_gbs": round(2.0 * Bn * n * 4 * D / (ms * 1e-3) / 1e9, 1)})
+    del qkv, o
+    # routed MLP (LN2 + gather, fc1 + GELU, fc2 + scatter-add), in place on a scratch copy
+    xs = x0.clone()
+    ms = run(lambda: B.ssam_routed_mlp(xs, keep, w0["ln2_g"], w0["ln2_b"], 1e-6, w0["w1"], w0["b1"], w0["w2"], w0["b2"],
+                                       workspace=ws_buf))
+    parts["routed_mlp"] = mfma(ms, 4.0 * Bn * K * D * Dm)
+    # scores (one read of x) and keep-set selection (latency bound: microseconds, once per image for all blocks)
+    ms = run(lambda: B.ssam_score_tokens(x0.view(Bn, g, g, D), scores=scores, workspace=ws_buf))
+    parts["score_tokens"] = hbm(ms, 2.0 * Bn * n * D)
+    ms = run(lambda: B.ssam_select_tokens(scores, K, keep_idx=keep))
+    parts["select_tokens"] = {"us": round(ms * 1e3, 1), "bound": "latency", "once_per": "image, shared by all blocks"}
+    return parts
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -189,13 +278,18 @@ def main():
         evs = None
         if with_events:
             evs = [(C.c_void_p * (2 * shape.depth))(*[hip.event() for _ in range(2 * shape.depth)]) for _ in range(steps)]
+        marks = [hip.event() for _ in range(steps + 1)]
+        stream = torch.cuda.current_stream().cuda_stream
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        hip.record(marks[0], stream)
         for s in range(steps):
             step(cl, cg, kp, evs[s] if evs else None)
+            hip.record(marks[s + 1], stream)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        return dt, evs
+        per_step = [hip.elapsed_ms(marks[s], marks[s + 1]) for s in range(steps)]
+        return dt, evs, per_step
 
     if args.calibrate_copy:
         ident = torch.arange(n, dtype=torch.int32, device=dev)
@@ -204,7 +298,7 @@ def main():
             B.ssam_permute(x0, ident, ycopy)           # reads and writes B*N*D*2 bytes each
         torch.cuda.synchronize()
 
-    dt, evs = timed(cfg_l, cfg_g, keep, args.steps, args.warmup, True)
+    dt, evs, per_step = timed(cfg_l, cfg_g, keep, args.steps, args.warmup, True)
     ms_per_step = dt / args.steps * 1e3
     images_per_s = Bn * args.steps / dt
     assert torch.isfinite(x.float()).all().item(), "non-finite encoder output"
@@ -230,7 +324,8 @@ def main():
     out = {
         "metric": "ViT-H encoder images/sec at density 0.4 (1 GPU); sparse-attn/MLP MFMA util %",
         "value": round(images_per_s, 3), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 3), "ms_per_step_median": round(float(np.median(per_step)), 3),
+        "ms_per_step_min": round(float(np.min(per_step)), 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"SAM {shape.name} encoder blocks, batch {Bn}, 64x64 tokens, window 14, "
                                f"global blocks {list(shape.global_blocks)}, density {r} (attention and MLP)",
@@ -240,37 +335,54 @@ def main():
         "roofline": roofline,
     }
 
-    # ---- dense GPU block: the same kernels at r = rho = 1
+    # ---- the other entry points, one by one (HIP events around `reps` back-to-back calls)
+    if not args.no_parts:
+        out["parts"] = time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab, keep, scores, ws_buf)
+
+    # ---- dense GPU block (the same kernels at r = rho = 1) and density 0.3
     if not args.no_dense:
         keep_dense.copy_(torch.arange(n, dtype=torch.int32, device=dev).expand(Bn, n))
         dsteps = max(2, args.steps // 2)
-        ddt, _ = timed(cfg_ld, cfg_gd, keep_dense, dsteps, 1, False)
+        ddt, _, _ = timed(cfg_ld, cfg_gd, keep_dense, dsteps, 1, False)
         d_ms = ddt / dsteps * 1e3
         out["dense"] = {"ms_per_step": round(d_ms, 3), "images_per_s": round(Bn * dsteps / ddt, 3),
                         "speedup_sparse_over_dense": round(d_ms / ms_per_step, 3)}
+        if abs(r - 0.3) > 1e-9:
+            K3 = B.ssam_keep_count(n, 0.3)
+            cfg_l3, cfg_g3 = make_cfgs(0.3, K3)
+            keep3 = torch.empty((Bn, K3), dtype=torch.int32, device=dev)
+            tdt, _, _ = timed(cfg_l3, cfg_g3, keep3, dsteps, 1, False)
+            out["density_0.3"] = {"ms_per_step": round(tdt / dsteps * 1e3, 3), "images_per_s": round(Bn * dsteps / tdt, 3),
+                                  "keep": K3, "speedup_over_dense": round(d_ms / (tdt / dsteps * 1e3), 3)}
 
     # ---- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         import oracle
-        wl = {k: v.float().cpu().numpy() for k, v in wts[0].items()}
         xi = x_host[0]
+        n_glob = len(shape.global_blocks)
+        loc = [i for i in range(shape.depth) if i not in shape.global_blocks][:10]
+        glo = list(shape.global_blocks)[:3]
         t0 = time.perf_counter()
         keep_o = oracle.select_tokens(oracle.score_tokens(xi), oracle.keep_count(n, rho))
-        oracle.encoder_block(xi, oracle.BlockWeights(**wl), shape.heads, shape.ws, 4, 32, r, keep_o)
-        t_local = time.perf_counter() - t0
-        gi = shape.global_blocks[0]
-        wg = {k: v.float().cpu().numpy() for k, v in wts[gi].items()}
+        t_sel = time.perf_counter() - t0
+        y = xi
         t0 = time.perf_counter()
-        oracle.encoder_block(xi, oracle.BlockWeights(**wg), shape.heads, 0, 4, 128, r, keep_o)
-        t_global = time.perf_counter() - t0
-        n_glob = len(shape.global_blocks)
-        t_image = t_local * (shape.depth - n_glob) + t_global * n_glob
+        for i in loc:
+            wl = {k: v.float().cpu().numpy() for k, v in wts[i].items()}
+            y = oracle.encoder_block(y, oracle.BlockWeights(**wl), shape.heads, shape.ws, 4, 32, r, keep_o)
+        t_local = (time.perf_counter() - t0) / len(loc)
+        t0 = time.perf_counter()
+        for i in glo:
+            wg = {k: v.float().cpu().numpy() for k, v in wts[i].items()}
+            y = oracle.encoder_block(y, oracle.BlockWeights(**wg), shape.heads, 0, 4, 128, r, keep_o)
+        t_global = (time.perf_counter() - t0) / len(glo)
+        t_image = t_sel + t_local * (shape.depth - n_glob) + t_global * n_glob
         out["cpu_baseline"] = {
             "value": round(1.0 / t_image, 6), "unit": "images/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
             "kind": "oracle",
-            "sample": f"one image: scores + keep-set + 1 windowed block ({t_local:.2f} s) and 1 global block "
-                      f"({t_global:.2f} s) at full {shape.name} size; images/s extrapolated as "
-                      f"1/({shape.depth - n_glob}*t_local + {n_glob}*t_global)",
+            "sample": f"one image at full {shape.name} size: scores + keep-set ({t_sel:.2f} s), {len(loc)} windowed blocks "
+                      f"({t_local:.2f} s each) and {len(glo)} global blocks ({t_global:.2f} s each), host-to-numpy weight "
+                      f"conversion included; images/s extrapolated as 1/(t_sel + {shape.depth - n_glob}*t_local + {n_glob}*t_global)",
         }
     print(json.dumps(out))
 
