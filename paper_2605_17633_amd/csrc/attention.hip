@@ -76,10 +76,10 @@ __device__ __forceinline__ void init_state(WaveState<D> &st)
 //   tq[q*2*ts + p]      = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
 //   tq[q*2*ts + ts + p] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
 // rel tables: rows of `rstr` elements, from global memory (rstr = D) or from a zero-padded LDS copy.
-template <int D>
+template <int D, typename TabT>
 __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr,
                                                 bool rows_padded, int w, int qrow, int qcol,
-                                                float *tq, int ts)
+                                                TabT *tq, int ts)
 {
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int nrel = 2 * w - 1;
@@ -100,13 +100,13 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
                 if (ok) a = *reinterpret_cast<const bf16x8 *>(rel + (long)mrow * rstr + ks * 16 + half * 8);
                 u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], u, 0, 0, 0);
             }
-            float *dst = tq + l32 * 2 * ts + (tab ? ts : 0);
+            TabT *dst = tq + l32 * 2 * ts + (tab ? ts : 0);
             const int qpos = tab ? qcol : qrow;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int m = mt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 int p = qpos + (w - 1) - m;
-                if (p >= 0 && p < w && m < nrel) dst[p] = u[r] * LOG2E;
+                if (p >= 0 && p < w && m < nrel) dst[p] = (TabT)(u[r] * LOG2E);
             }
         }
     }
@@ -118,10 +118,10 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
 //           low half = 4*row, high half = 4*(ts + col); indexed like Ks
 //   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
 //   tq:     this lane's query row of the bias table
-template <int D, int NB, bool RAGGED>
+template <int D, int NB, bool RAGGED, typename TabT>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
-                                                int S, float scale_log2e, const float *tq)
+                                                int S, float scale_log2e, const TabT *tq)
 {
     using C = AttnCfg<D>;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
@@ -151,8 +151,8 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * g + e;
                     const uint32_t c = rc[e];
-                    const float bh = *reinterpret_cast<const float *>(tqb + (c & 0xffffu));
-                    const float bw = *reinterpret_cast<const float *>(tqb + (c >> 16));
+                    const float bh = (float)*reinterpret_cast<const TabT *>(tqb + (c & 0xffffu));
+                    const float bw = (float)*reinterpret_cast<const TabT *>(tqb + (c >> 16));
                     float val = s[b][r] * scale_log2e + bh + bw;
                     if (RAGGED) val = (key0[b] + 8 * g + 4 * half + e < S) ? val : -INFINITY;
                     s[b][r] = val;
@@ -262,17 +262,17 @@ __device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int
 }
 
 // the same as byte offsets into a query's bias table row (th part, then tw part at +ts floats)
-__device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p, int S, int w, int ts)
+__device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p, int S, int w, int ts, uint32_t esz = 4u)
 {
     uint32_t rc = key_row_col(sigma, p, S, w);
-    return (4u * (rc & 0xffffu)) | ((4u * ((uint32_t)ts + (rc >> 16))) << 16);
+    return (esz * (rc & 0xffffu)) | ((esz * ((uint32_t)ts + (rc >> 16))) << 16);
 }
 
 // per-wave LDS scratch: the bias rows of its 32 queries, later overlaid by its output staging tile
 template <int D>
-__host__ __device__ inline int wave_scratch_bytes(int ts)
+__host__ __device__ inline int wave_scratch_bytes(int ts, int esz = 4)
 {
-    int bias = 32 * 2 * ts * 4, stage = 32 * AttnCfg<D>::KSTR * 2;
+    int bias = 32 * 2 * ts * esz, stage = 32 * AttnCfg<D>::KSTR * 2;
     return ((bias > stage ? bias : stage) + 15) & ~15;
 }
 
@@ -292,7 +292,7 @@ constexpr int WIN_MAX_LOADS = 5;     // 16-byte K (and V) chunks per thread: 224
 
 template <int D>
 __global__ void __launch_bounds__(448)
-attn_window_kernel(AttnParams P, int n_problems)
+attn_window_kernel(AttnParams P, int n_groups)
 {
     using C = AttnCfg<D>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -343,9 +343,15 @@ attn_window_kernel(AttnParams P, int n_problems)
         load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);                              \
     }
 
-    int prob = blockIdx.x;
-    if (prob < n_problems) WIN_PREFETCH(prob)
-    for (; prob < n_problems; prob += gridDim.x) {
+    // Problems are dealt so that the heads of one window run on one XCD (workgroup b sits on XCD b & 7):
+    // a head's rows are 2*D bytes at a stride of the packed row, so neighbouring heads share cache lines,
+    // and those are then fetched into one L2 instead of eight.  XCD x takes windows x, x+8, ..., heads fastest.
+    const int xcd = blockIdx.x & 7, nslots = ((int)gridDim.x - xcd + 7) >> 3;
+    auto local_problem = [&](int lp) { int g = xcd + 8 * (lp / P.h); return g < n_groups ? g * P.h + lp % P.h : -1; };
+    int lp = blockIdx.x >> 3;
+    int prob = local_problem(lp);
+    if (prob >= 0) WIN_PREFETCH(prob)
+    for (; prob >= 0; lp += nslots, prob = local_problem(lp)) {
         const int grp = prob / P.h, head = prob % P.h;
         LDS_BARRIER();                            // every wave is done with the previous problem's LDS (output stores stay in flight)
 #pragma unroll
@@ -358,8 +364,8 @@ attn_window_kernel(AttnParams P, int n_problems)
         }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) qf[ks] = qnext[ks];
-        if (prob + (int)gridDim.x < n_problems) WIN_PREFETCH(prob + (int)gridDim.x)
-        build_bias_rows<D>(qf, Rh, Rw, C::KSTR, true, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+        if (local_problem(lp + nslots) >= 0) WIN_PREFETCH(local_problem(lp + nslots))
+        build_bias_rows<D, float>(qf, Rh, Rw, C::KSTR, true, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
         LDS_BARRIER();
 
         WaveState<D> st;
@@ -378,9 +384,9 @@ attn_window_kernel(AttnParams P, int n_problems)
 #pragma unroll
             for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
             if (ragged)
-                attn_chunk_step<D, WIN_NB, true>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, WIN_NB, true, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
             else
-                attn_chunk_step<D, WIN_NB, false>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, WIN_NB, false, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
         }
         finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + q0) * ((long)P.h * D) + (long)head * D,
                             (long)P.h * D, min(32, S - q0));
@@ -389,17 +395,22 @@ attn_window_kernel(AttnParams P, int n_problems)
 
 // ------------------------------------------------------------------ global kernel
 constexpr int GLB_TILE = 128;
+constexpr int GLB_NB = 2;              // key blocks per softmax chunk (register budget: 2 waves per SIMD)
+// Bias rows of the global kernel are held as fp16 (11 significant bits on log2e * q.r, below the bf16
+// rounding of the probabilities that feed the second product): at w = 64 that brings a workgroup to
+// 78 KB of LDS, so two workgroups share a CU and one hides the other's LDS, MFMA and barrier latency.
+typedef _Float16 GlbTab;
 
 template <int D>
 size_t global_lds_bytes(int w)
 {
     int ts = w | 1;
-    return (size_t)2 * GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)4 * wave_scratch_bytes<D>(ts) + (size_t)GLB_TILE * 4;
+    return (size_t)2 * GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)4 * wave_scratch_bytes<D>(ts, sizeof(GlbTab)) + (size_t)GLB_TILE * 4;
 }
 
 template <int D>
-__global__ void __launch_bounds__(256)
-attn_global_kernel(AttnParams P, int T)
+__global__ void __launch_bounds__(256, 2)
+attn_global_kernel(AttnParams P, int T, int n_gh)
 {
     using C = AttnCfg<D>;
     constexpr int LOADS = GLB_TILE * C::CH / 256;       // 16-byte chunks per thread per operand
@@ -409,10 +420,13 @@ attn_global_kernel(AttnParams P, int T)
     bf16 *Ks = reinterpret_cast<bf16 *>(smem);
     bf16 *Vs = Ks + GLB_TILE * C::KSTR;
     unsigned char *Tb = reinterpret_cast<unsigned char *>(Vs + GLB_TILE * C::KSTR);
-    const int wsb = wave_scratch_bytes<D>(ts);
+    const int wsb = wave_scratch_bytes<D>(ts, sizeof(GlbTab));
     uint32_t *krc = reinterpret_cast<uint32_t *>(Tb + 4 * wsb);
 
-    const int qt = blockIdx.x % T, gh = blockIdx.x / T;
+    // the query tiles of one (image, head) run on one XCD (workgroup b sits on XCD b & 7), whose L2 then
+    // serves the re-reads of that problem's K and V tiles
+    const int qt = (blockIdx.x >> 3) % T, gh = ((blockIdx.x >> 3) / T) * 8 + (blockIdx.x & 7);
+    if (gh >= n_gh) return;
     const int grp = gh / P.h, head = gh % P.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31;
     const int S = P.S;
@@ -423,7 +437,7 @@ attn_global_kernel(AttnParams P, int T)
     bf16x8 qf[C::KS];
     load_q_frags<D>(qf, P.q + base + (long)qclamp * P.row_stride);
     const uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
-    float *tq = reinterpret_cast<float *>(Tb + wave * wsb);
+    GlbTab *tq = reinterpret_cast<GlbTab *>(Tb + wave * wsb);
 
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
     u32x4 rk[LOADS], rv[LOADS];
@@ -439,7 +453,7 @@ attn_global_kernel(AttnParams P, int T)
             rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8);    \
             rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8);    \
         }                                                                                               \
-        if (tid < GLB_TILE) rrc = key_bias_offsets(P.sigma, key0_ + tid, S, P.w, ts);                   \
+        if (tid < GLB_TILE) rrc = key_bias_offsets(P.sigma, key0_ + tid, S, P.w, ts, sizeof(GlbTab));   \
     }
 #define ATTN_STORE_TILE()                                                                               \
     {                                                                                                   \
@@ -453,7 +467,7 @@ attn_global_kernel(AttnParams P, int T)
     }
 
     ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt)          // in flight while the bias rows are formed
-    build_bias_rows<D>(qf, P.rel_h, P.rel_w, D, false, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+    build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, false, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
 
     WaveState<D> st;
     init_state<D>(st);
@@ -463,13 +477,19 @@ attn_global_kernel(AttnParams P, int T)
         ATTN_STORE_TILE()
         LDS_BARRIER();
         if (a + 1 < nact) ATTN_LOAD_TILE(a + 1 < P.n_pre ? a + 1 : qt)
-        const int blk[4] = { 0, 1, 2, 3 };
-        const int key0[4] = { kt * GLB_TILE, kt * GLB_TILE + 32, kt * GLB_TILE + 64, kt * GLB_TILE + 96 };
-        const int nb = min(4, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
-        if (kt * GLB_TILE + GLB_TILE > S)
-            attn_chunk_step<D, 4, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
-        else
-            attn_chunk_step<D, 4, false>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+        const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
+#pragma unroll
+        for (int c0 = 0; c0 < GLB_TILE / 32; c0 += GLB_NB) {
+            if (c0 >= nblk) break;
+            int blk[GLB_NB], key0[GLB_NB];
+#pragma unroll
+            for (int b = 0; b < GLB_NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
+            const int nb = min(GLB_NB, nblk - c0);
+            if (key0[GLB_NB - 1] + 32 > S)
+                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+            else
+                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+        }
     }
     const int qw0 = qt * GLB_TILE + wave * 32;
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + qw0) * ((long)P.h * D) + (long)head * D,
@@ -494,7 +514,7 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
         if (per_cu < 1) per_cu = 1;
         if (per_cu > 4) per_cu = 4;
         int grid = n_problems < 256 * per_cu ? n_problems : 256 * per_cu;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(nqb * 64), lds, st, P, n_problems);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(nqb * 64), lds, st, P, groups);
     } else {
         int T = ssam_div_up(P.S, GLB_TILE);
         size_t lds = global_lds_bytes<D>(P.w);
@@ -503,7 +523,7 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
         if (lds > 64 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return SSAM_EHIP;
-        hipLaunchKernelGGL(kern, dim3((unsigned)((long)T * groups * P.h)), dim3(256), lds, st, P, T);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((long)T * ssam_div_up(groups * P.h, 8) * 8)), dim3(256), lds, st, P, T, groups * P.h);
     }
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
@@ -525,7 +545,7 @@ extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v
     if (mask_block == 32) {
         if (S > 224) return SSAM_EUNSUPPORTED;
     } else if (mask_block == 128) {
-        if (S > 16384 || (long)ssam_div_up(S, 128) * groups * h > 0x7fffffffL) return SSAM_EUNSUPPORTED;
+        if (S > 16384 || (long)ssam_div_up(S, 128) * ((long)groups * h + 7) > 0x7fffffffL) return SSAM_EUNSUPPORTED;
     } else {
         return SSAM_EUNSUPPORTED;
     }
