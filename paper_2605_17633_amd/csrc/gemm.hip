@@ -23,19 +23,19 @@ TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes
     return p;
 }
 
-template <int BM, int BN, int EPI, int SUB_M, int SUB_N>
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N, int WGM = 2, int WGN = 2>
 int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
                  const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm, const GemmSplit &sp, hipStream_t st)
 {
     if (tr.tile_count <= 0) return SSAM_OK;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, WGM, WGN>();
+    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN>;
     // more than 64 KiB of LDS per workgroup needs the per-kernel opt-in (idempotent, host-side only)
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SSAM_EHIP;
     int per_xcd = ssam_div_up((long)tr.tile_count * SUB_M * SUB_N * sp.parts, 8);
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(GEMM_THREADS), lds, st, A, W, bias, C, M, N, K, ld, tr, rm, sp);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WGM * WGN), lds, st, A, W, bias, C, M, N, K, ld, tr, rm, sp);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }
@@ -43,7 +43,7 @@ int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
 // Whole rounds of BM x BN tiles, then the left-over tiles (when they would fill less than half a round)
 // as TM x TN tiles, BM = SUB_M*TM, BN = SUB_N*TN.  slots = workgroups the chip runs at once with the large
 // tile.  With a workspace, a long K and few left-over tiles, the left-over launch also cuts K (see the kernel).
-template <int BM, int BN, int TM, int TN, int EPI>
+template <int BM, int BN, int TM, int TN, int EPI, int WGM = 2, int WGN = 2>
 int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
                  const GemmLd &ld, int slots, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
@@ -55,7 +55,7 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
     const TailPlan plan = plan_tail(total, slots, nk, SUB_M * SUB_N, (size_t)TM * TN * sizeof(float), ws);
     const int rem = plan.rem, parts = plan.parts;
     tr.tile_count = total - rem;
-    int rc = launch_range<BM, BN, EPI, 1, 1>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
     if (rc != SSAM_OK || rem == 0) return rc;
     tr.tile_begin = total - rem;
     tr.tile_count = rem;
@@ -78,22 +78,23 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
                 const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
     switch (tile) {
-    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
+    case 4: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     default: return SSAM_EINVAL;
     }
 }
 
 // Pick the tile by a time model in microseconds, fitted on MI355X to the ViT-H layer shapes: a round of
-// workgroups costs nk * t_slab + t_epi (the 256x256 tile reads least LDS per flop but runs one workgroup
-// per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one workgroup's
-// epilogue behind the other's main loop); the
+// workgroups costs nk * t_slab + t_epi (the 256x256 tile, eight waves, moves least data per flop but runs
+// one workgroup per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one
+// workgroup's epilogue behind the other's main loop); the
 // left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
 int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
 {
     struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[3]; };
-    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.80, { 8.0, 17.8, 18.7 } },
+    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5 } },
                             { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5 } },
                             { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8 } } };
     const int nk = K / GEMM_BK;
@@ -145,7 +146,7 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, co
     if (lda < K || ldw < K || ldc < N || lda % 8 || ldw % 8 || ldc % 8) return SSAM_EINVAL;
     if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
     if (N % 128 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
-    if (tile < 0 || tile > 3) return SSAM_EINVAL;
+    if (tile < 0 || tile > 4) return SSAM_EINVAL;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
     if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD) {
         if (!row_map || rows_per_batch <= 0 || map_batch_stride < 0 || dst_rows_per_batch <= 0) return SSAM_EINVAL;

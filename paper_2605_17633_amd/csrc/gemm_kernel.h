@@ -2,8 +2,10 @@
 // 32x32x16 bf16 MFMA.  Serves the block's qkv / proj / fc1 / fc2 layers (the dense contractions
 // of the SAM block; the routed MLP of Sec. 4.2 reaches it with the gathered keep-set rows as A).
 //
-// Workgroup = 256 threads = 4 waves in a 2x2 grid over a BM x BN tile; each wave owns
-// (BM/2) x (BN/2) as 32x32 MFMA tiles.  K is consumed in slabs of 64: global -> registers
+// Workgroup = WGM x WGN waves in a grid over a BM x BN tile; each wave owns (BM/WGM) x (BN/WGN) as
+// 32x32 MFMA tiles.  The 256x256 tile runs 8 waves (2x4, wave tile 128x64, under 256 VGPRs): two waves
+// per SIMD, so one wave's LDS, barrier and MFMA-result latency is covered by the other; the smaller
+// tiles run 4 waves (2x2) and two workgroups per CU.  K is consumed in slabs of 64: global -> registers
 // (prefetch of the next slab) -> LDS (double buffered; 16-byte chunks XOR-swizzled so that both
 // the staging writes and the ds_read_b128 fragment reads are bank-conflict free).  Fragments are
 // double buffered in registers and the instruction mix is pinned with sched_group_barrier so that
@@ -37,11 +39,11 @@ struct GemmRowMap {
 constexpr int GEMM_BK = 64;
 constexpr int GEMM_THREADS = 256;
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM = 2, int WGN = 2>
 constexpr size_t gemm_lds_bytes()
 {
     size_t pipe = (size_t)2 * (BM + BN) * GEMM_BK * sizeof(bf16);
-    size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float) + BM * sizeof(int);   // staging + scatter rows
+    size_t epi = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) + BM * sizeof(int);   // staging + scatter rows
     return pipe > epi ? pipe : epi;
 }
 
@@ -79,13 +81,15 @@ __device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t,
     n0 = (tn * sub_n + sub % sub_n) * bn;
 }
 
-template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1>
-__global__ void __launch_bounds__(GEMM_THREADS)
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2>
+__global__ void __launch_bounds__(64 * WGM * WGN)
 gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                     bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
 {
-    constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
-    constexpr int A_LOADS = BM * 8 / GEMM_THREADS, B_LOADS = BN * 8 / GEMM_THREADS;
+    constexpr int THREADS = 64 * WGM * WGN, RSTEP = THREADS / 8;   // waves in a WGM x WGN grid; rows staged per pass
+    constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
+    constexpr int A_LOADS = BM * 8 / THREADS, B_LOADS = BN * 8 / THREADS;
+    static_assert(BM % RSTEP == 0 && BN % RSTEP == 0 && RSTEP % 16 == 0, "staging passes must tile the operands");
     constexpr int NM = MT * NT, NR = MT + NT, NL = A_LOADS + B_LOADS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16 *As = reinterpret_cast<bf16 *>(smem);                 // [2][BM*64]
@@ -105,7 +109,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     if (m0 >= M) return;                        // a sub-tile wholly below the last row
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+    const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
     const int l32 = lane & 31, half = lane >> 5;
     const int nk = K / GEMM_BK;
     const int kb = (int)((long)nk * kpart / parts), ke = (int)((long)nk * (kpart + 1) / parts);   // this workgroup's slabs
@@ -121,14 +125,14 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     u32x4 ra[A_LOADS], rb[B_LOADS];
     bf16x8 af[2][MT], bfr[2][NT];
 
-    // staging: thread owns chunk c0 of rows r0 + 32*i of both operands
+    // staging: thread owns chunk c0 of rows r0 + RSTEP*i of both operands
     const int r0 = tid >> 3, c0 = tid & 7;
     const bf16 *ga[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i)          // rows past M repeat the last row; their results are never stored
-        ga[i] = A + (long)min(m0 + r0 + 32 * i, M - 1) * ld.a + c0 * 8;
+        ga[i] = A + (long)min(m0 + r0 + RSTEP * i, M - 1) * ld.a + c0 * 8;
     const bf16 *gb = W + (long)(n0 + r0) * ld.w + c0 * 8;
-    const int lst = gemm_swz(r0, c0);          // + i*32*64: rows 32 apart share the swizzle term
+    const int lst = gemm_swz(r0, c0);          // + i*RSTEP*64: rows a multiple of 16 apart share the swizzle term
     const int fa0 = (wm + l32) * GEMM_BK, fb0 = (wn + l32) * GEMM_BK;
     const int sw = (l32 >> 1) & 7;
 
@@ -137,15 +141,15 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
             ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + (kt_) * GEMM_BK);                        \
         _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
-            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * 32 * ld.w + (kt_) * GEMM_BK);        \
+            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * RSTEP * ld.w + (kt_) * GEMM_BK);        \
     }
 #define GEMM_STORE_LDS(buf_)                                                                          \
     {                                                                                                 \
         bf16 *as_ = As + (buf_) * BM * GEMM_BK + lst, *bs_ = Bs + (buf_) * BN * GEMM_BK + lst;        \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
-            *reinterpret_cast<u32x4 *>(as_ + i * 32 * GEMM_BK) = ra[i];                               \
+            *reinterpret_cast<u32x4 *>(as_ + i * RSTEP * GEMM_BK) = ra[i];                               \
         _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
-            *reinterpret_cast<u32x4 *>(bs_ + i * 32 * GEMM_BK) = rb[i];                               \
+            *reinterpret_cast<u32x4 *>(bs_ + i * RSTEP * GEMM_BK) = rb[i];                               \
     }
 #define GEMM_LOAD_FRAGS(buf_, ks_, slot_)                                                             \
     {                                                                                                 \
@@ -227,7 +231,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     // old values of a whole 32-row slice are requested before the slice is staged, so that the slice pays
     // one memory round trip instead of one per pass.
     constexpr int PASSES = 32 / RPP;
-    int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + 4 * 32 * EPS);   // [BM], -1 = skip
+    int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + WGM * WGN * 32 * EPS);   // [BM], -1 = skip
     if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
         int mine = -1;
         if (tid < BM && m0 + tid < M) {

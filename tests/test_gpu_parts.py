@@ -128,7 +128,7 @@ def _gemm_ref(A, W, b):
     return A.astype(np.float64) @ W.astype(np.float64).T + b.astype(np.float64)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("M,N,K", [(300, 256, 64), (1000, 512, 192), (513, 768, 768), (64, 256, 128)])
 def test_linear_bias_and_gelu(tile, M, N, K):
     announce("linear", tile, M, N, K)
@@ -221,7 +221,7 @@ def test_linear_row_strides():
     assert e.value.code == B.EINVAL
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_linear_scatter_add(tile):
     announce("linear scatter", tile)
     rng = np.random.default_rng(6)
