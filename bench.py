@@ -247,7 +247,9 @@ def main():
     x_host = inputs.token_field(rng, Bn, g, shape.D)
     x0 = torch.from_numpy(x_host.reshape(Bn, n, shape.D)).to(dev).to(torch.bfloat16).contiguous()
     wts = device_weights(torch, args.seed + 1, shape, g, dev)
-    structs = [B.block_weights_struct(w) for w in wts]
+    # the four Linear weights of every block go into MFMA fragment order once, at load time (ssam_pack_weight)
+    wts_packed = [B.pack_block_weights(w) for w in wts]
+    structs = [B.block_weights_struct(w) for w in wts_packed]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)
     wtab = torch.from_numpy(B.ssam_build_window_table(g, shape.ws, 4)).to(dev)

@@ -143,10 +143,22 @@ int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, 
  * of the fp32 sum.  The workspace is scratch: contents undefined afterwards,
  * concurrent calls need separate workspaces. */
 size_t ssam_linear_workspace_bytes(void);
-int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, const float *bias, void *C, int ldc,
+int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed, const float *bias, void *C, int ldc,
                    int M, int N, int K, int epilogue, const int32_t *row_map, int rows_per_batch,
                    int map_batch_stride, int dst_rows_per_batch, int tile,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Weights in MFMA fragment order.  A weight matrix is static, so it can be laid
+ * out once the way the matrix cores consume it: Wp[N/32][K/16][64][8] bf16 with
+ *   Wp[nb][ks][32*hf + l][e] = W[32*nb + l][16*ks + 8*hf + e],
+ * i.e. the 1 KB operand-B fragment of every (32 output channels, 16 input
+ * channels) cell is contiguous.  ssam_linear_ld with w_packed != 0 (then ldw is
+ * ignored) loads such fragments straight into registers and stages only A in
+ * LDS, which halves its LDS traffic; results are bit-identical to the row-major
+ * form.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 32 ==
+ * 0 and K % 16 == 0 (else SSAM_EUNSUPPORTED); W and Wp must not overlap.  Tile
+ * 2 (256x128) has no packed form (SSAM_EUNSUPPORTED when forced). */
+int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Stripe-Sort attention (App. A.1, Alg. 1)                                  */
@@ -214,6 +226,7 @@ typedef struct ssam_block_weights {     /* every pointer: dev */
     const float *b1;                    /* [Dm] fp32                                 */
     const void *w2;                     /* bf16 [D][Dm]                              */
     const float *b2;                    /* [D] fp32                                  */
+    int packed;                         /* != 0: wqkv, wproj, w1, w2 are in the fragment order of ssam_pack_weight */
 } ssam_block_weights;
 
 typedef struct ssam_block_cfg {

@@ -27,10 +27,12 @@ class SsamError(RuntimeError):
         super().__init__(f"{name}: {status_string(code)} ({code})")
 
 
+_WEIGHT_POINTERS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj", "bproj",
+                    "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
 class BlockWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in (
-        "ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj", "bproj",
-        "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")]
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_POINTERS] + [("packed", C.c_int)]
 
 
 class BlockCfg(C.Structure):
@@ -178,8 +180,9 @@ def _rows(t, dtype, name):
 
 
 def ssam_linear_ld(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows_per_batch=1, map_batch_stride=0,
-                   dst_rows_per_batch=1, tile=0, workspace=None):
-    """ssam_linear on operands with their own row strides, with an optional scratch workspace (uint8)."""
+                   dst_rows_per_batch=1, tile=0, workspace=None, w_packed=False):
+    """ssam_linear on operands with their own row strides, with an optional scratch workspace (uint8);
+    w_packed: W is the output of ssam_pack_weight."""
     M, K = A.shape
     N = W.shape[0]
     assert W.shape[1] == K
@@ -187,7 +190,7 @@ def ssam_linear_ld(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows
         C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
     (pa, lda), (pw, ldw), (pc, ldc) = _rows(A, torch.bfloat16, "A"), _rows(W, torch.bfloat16, "W"), _rows(C_out, torch.bfloat16, "C")
     _check("ssam_linear_ld", lib().ssam_linear_ld(
-        pa, lda, pw, ldw, _f32(bias, "bias"), pc, ldc, C.c_int(M), C.c_int(N), C.c_int(K),
+        pa, lda, pw, ldw, C.c_int(1 if w_packed else 0), _f32(bias, "bias"), pc, ldc, C.c_int(M), C.c_int(N), C.c_int(K),
         C.c_int(epilogue), _i32(row_map, "row_map"), C.c_int(rows_per_batch), C.c_int(map_batch_stride),
         C.c_int(dst_rows_per_batch), C.c_int(tile), _dev(workspace, torch.uint8, "workspace"),
         C.c_size_t(0 if workspace is None else workspace.numel()), _stream()))
@@ -259,22 +262,45 @@ def ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, workspace=None
 _BF16_FIELDS = ("wqkv", "rel_h", "rel_w", "wproj", "w1", "w2")
 
 
-def upload_block_weights(wdict: dict, device="cuda") -> dict:
+_PACKABLE = ("wqkv", "wproj", "w1", "w2")
+
+
+def ssam_pack_weight(W, Wp=None):
+    """Row-major [N][K] bf16 weight -> MFMA fragment order (same shape and bytes, different order)."""
+    N, K = W.shape
+    pw, ldw = _rows(W, torch.bfloat16, "W")
+    if Wp is None:
+        Wp = torch.empty((N, K), dtype=torch.bfloat16, device=W.device)
+    _check("ssam_pack_weight", lib().ssam_pack_weight(pw, ldw, _bf(Wp, "Wp"), C.c_int(N), C.c_int(K), _stream()))
+    return Wp
+
+
+def pack_block_weights(wt: dict) -> dict:
+    """Device weight dict -> the same with the four Linear weights in fragment order (flagged 'packed')."""
+    out = dict(wt)
+    for k in _PACKABLE:
+        out[k] = ssam_pack_weight(wt[k])
+    out["packed"] = True
+    return out
+
+
+def upload_block_weights(wdict: dict, device="cuda", pack=False) -> dict:
     """numpy fp32 dict (bf16-representable values) -> device tensors in the ABI's dtypes."""
     out = {}
     for k, v in wdict.items():
         t = torch.from_numpy(np.ascontiguousarray(v))
         out[k] = t.to(device=device, dtype=torch.bfloat16 if k in _BF16_FIELDS else torch.float32).contiguous()
-    return out
+    return pack_block_weights(out) if pack else out
 
 
 def block_weights_struct(wt: dict) -> BlockWeights:
     s = BlockWeights()
-    for name, _ in BlockWeights._fields_:
+    for name in _WEIGHT_POINTERS:
         t = wt[name]
         want = torch.bfloat16 if name in _BF16_FIELDS else torch.float32
         _dev(t, want, name)
         setattr(s, name, t.data_ptr())
+    s.packed = 1 if wt.get("packed") else 0
     return s
 
 

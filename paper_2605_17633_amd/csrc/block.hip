@@ -6,7 +6,7 @@
 #include "gemm_kernel.h"
 
 int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
-                     const GemmLd &ld, int epilogue, const GemmRowMap &rm, int tile,
+                     const GemmLd &ld, bool packed, int epilogue, const GemmRowMap &rm, int tile,
                      void *split_ws, size_t split_ws_bytes, hipStream_t st);
 
 namespace {
@@ -47,10 +47,10 @@ extern "C" size_t ssam_routed_mlp_workspace_bytes(int B, int K, int D, int Dm)
     return mlp_ws_bytes(B, K, D, Dm);
 }
 
-extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
-                               const void *w1, const float *b1, const void *w2, const float *b2,
-                               int B, int N, int D, int Dm, int K,
-                               void *workspace, size_t workspace_bytes, void *stream)
+static int routed_mlp_impl(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                           const void *w1, const float *b1, const void *w2, const float *b2, bool packed,
+                           int B, int N, int D, int Dm, int K,
+                           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!x || !keep_idx || !ln_g || !ln_b || !w1 || !b1 || !w2 || !b2 || !workspace) return SSAM_EINVAL;
     if (B <= 0 || N <= 0 || D <= 0 || Dm <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
@@ -65,11 +65,19 @@ extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln
     int rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
-    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, SSAM_EPI_BIAS_GELU, none, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, packed, SSAM_EPI_BIAS_GELU, none, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     GemmRowMap scatter = { keep_idx, K, K, N };
-    return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, GemmLd{ Dm, Dm, D }, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0,
+    return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, GemmLd{ Dm, Dm, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0,
                             split, GEMM_SPLIT_WS_BYTES, st);
+}
+
+extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                               const void *w1, const float *b1, const void *w2, const float *b2,
+                               int B, int N, int D, int Dm, int K,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return routed_mlp_impl(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, false, B, N, D, Dm, K, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
@@ -103,7 +111,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, SSAM_EPI_BIAS, none, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, w->packed != 0, SSAM_EPI_BIAS, none, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
@@ -112,9 +120,9 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
                                1.0f / sqrtf((float)g.d), stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap back = { gather_table, g.Nout, 0, g.N };
-    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, w->packed != 0, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
-    return ssam_routed_mlp(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2,
+    return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, w->packed != 0,
                            B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);
 }
 

@@ -23,13 +23,13 @@ TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes
     return p;
 }
 
-template <int BM, int BN, int EPI, int SUB_M, int SUB_N, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N, int WGM = 2, int WGN = 2, bool WPACK = false>
 int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
                  const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm, const GemmSplit &sp, hipStream_t st)
 {
     if (tr.tile_count <= 0) return SSAM_OK;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, WGM, WGN>();
-    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, WGM, WGN, WPACK>();
+    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK>;
     // more than 64 KiB of LDS per workgroup needs the per-kernel opt-in (idempotent, host-side only)
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -43,7 +43,7 @@ int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
 // Whole rounds of BM x BN tiles, then the left-over tiles (when they would fill less than half a round)
 // as TM x TN tiles, BM = SUB_M*TM, BN = SUB_N*TN.  slots = workgroups the chip runs at once with the large
 // tile.  With a workspace, a long K and few left-over tiles, the left-over launch also cuts K (see the kernel).
-template <int BM, int BN, int TM, int TN, int EPI, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int TM, int TN, int EPI, int WGM = 2, int WGN = 2, bool WPACK = false>
 int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
                  const GemmLd &ld, int slots, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
@@ -55,14 +55,14 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
     const TailPlan plan = plan_tail(total, slots, nk, SUB_M * SUB_N, (size_t)TM * TN * sizeof(float), ws);
     const int rem = plan.rem, parts = plan.parts;
     tr.tile_count = total - rem;
-    int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
     if (rc != SSAM_OK || rem == 0) return rc;
     tr.tile_begin = total - rem;
     tr.tile_count = rem;
     const int n_sub = rem * SUB_M * SUB_N;
     if (parts > 1) {
         const GemmSplit sp = { (float *)ws.ptr, parts };
-        rc = launch_range<TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N>(A, W, bias, C, M, N, K, ld, tr, rm, sp, st);
+        rc = launch_range<TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, sp, st);
         if (rc != SSAM_OK) return rc;
         constexpr int RPB = 256 / (TN / 8);
         hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
@@ -70,7 +70,18 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
         SSAM_CHECK_LAUNCH();
         return SSAM_OK;
     }
-    return launch_range<TM, TN, EPI, SUB_M, SUB_N>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    return launch_range<TM, TN, EPI, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+}
+
+template <int EPI>
+int launch_tile_packed(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
+                       const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
+{
+    switch (tile) {
+    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI, 2, 4, true>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 3: return launch_split<128, 128, 64, 128, EPI, 2, 2, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
+    default: return SSAM_EUNSUPPORTED;
+    }
 }
 
 template <int EPI>
@@ -91,7 +102,7 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
 // one workgroup per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one
 // workgroup's epilogue behind the other's main loop); the
 // left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
-int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
+int pick_tile(int M, int N, int K, int epilogue, bool packed, const SplitWs &ws)
 {
     struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[3]; };
     const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5 } },
@@ -101,11 +112,11 @@ int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
     int best = 3;
     double best_time = 1e30;
     for (const Cand &c : cands) {
-        if (N % c.bn != 0) continue;
+        if (N % c.bn != 0 || (packed && c.id == 2)) continue;
         const int subs = (c.bm / c.tm) * (c.bn / c.tn);
         const int total = ssam_div_up(M, c.bm) * (N / c.bn);
         const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
-        const double round = nk * c.t_slab + c.t_epi[epilogue];
+        const double round = nk * c.t_slab * (packed ? 0.93 : 1.0) + c.t_epi[epilogue];
         double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
         if (plan.rem != 0) {
             const int n_sub = plan.rem * subs;
@@ -119,13 +130,21 @@ int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
 }  // namespace
 
 int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
-                     const GemmLd &ld, int epilogue, const GemmRowMap &rm, int tile,
+                     const GemmLd &ld, bool packed, int epilogue, const GemmRowMap &rm, int tile,
                      void *split_ws, size_t split_ws_bytes, hipStream_t st)
 {
     const SplitWs ws = { split_ws, split_ws_bytes };
     const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
     bf16 *c = (bf16 *)C;
-    if (tile == 0) tile = pick_tile(M, N, K, epilogue, ws);
+    if (tile == 0) tile = pick_tile(M, N, K, epilogue, packed, ws);
+    if (packed) {
+        switch (epilogue) {
+        case SSAM_EPI_BIAS: return launch_tile_packed<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+        case SSAM_EPI_BIAS_GELU: return launch_tile_packed<SSAM_EPI_BIAS_GELU>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+        case SSAM_EPI_BIAS_SCATTER_ADD: return launch_tile_packed<SSAM_EPI_BIAS_SCATTER_ADD>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+        default: return SSAM_EINVAL;
+        }
+    }
     switch (epilogue) {
     case SSAM_EPI_BIAS: return launch_tile<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
     case SSAM_EPI_BIAS_GELU: return launch_tile<SSAM_EPI_BIAS_GELU>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
@@ -136,17 +155,43 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
 
 extern "C" size_t ssam_linear_workspace_bytes(void) { return GEMM_SPLIT_WS_BYTES; }
 
-extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, const float *bias, void *C, int ldc,
+__global__ void __launch_bounds__(256)
+pack_weight_kernel(const bf16 *__restrict__ W, int ldw, bf16 *__restrict__ Wp, int N, int K)
+{
+    // one thread per 16-byte chunk of the packed matrix: chunk id = ((nb*ksteps + ks)*64 + lane)
+    const long id = (long)blockIdx.x * 256 + threadIdx.x;
+    const int ksteps = K / 16;
+    if (id >= (long)(N / 32) * ksteps * 64) return;
+    const int lane = (int)(id & 63), l = lane & 31, hf = lane >> 5;
+    const long cell = id >> 6;
+    const int ks = (int)(cell % ksteps), nb = (int)(cell / ksteps);
+    reinterpret_cast<u32x4 *>(Wp)[id] = *reinterpret_cast<const u32x4 *>(W + (long)(32 * nb + l) * ldw + 16 * ks + 8 * hf);
+}
+
+extern "C" int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream)
+{
+    if (!W || !Wp || N <= 0 || K <= 0 || ldw < K || ldw % 8) return SSAM_EINVAL;
+    if (!ssam_aligned16(W) || !ssam_aligned16(Wp)) return SSAM_EINVAL;
+    if (N % 32 != 0 || K % 16 != 0) return SSAM_EUNSUPPORTED;
+    const long chunks = (long)N * K / 8;
+    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)ssam_div_up(chunks, 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16 *)W, ldw, (bf16 *)Wp, N, K);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed, const float *bias, void *C, int ldc,
                               int M, int N, int K, int epilogue, const int32_t *row_map, int rows_per_batch,
                               int map_batch_stride, int dst_rows_per_batch, int tile,
                               void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!A || !W || !bias || !C || M <= 0 || N <= 0 || K <= 0) return SSAM_EINVAL;
     if (!ssam_aligned16(A) || !ssam_aligned16(W) || !ssam_aligned16(bias) || !ssam_aligned16(C)) return SSAM_EINVAL;
-    if (lda < K || ldw < K || ldc < N || lda % 8 || ldw % 8 || ldc % 8) return SSAM_EINVAL;
+    if (lda < K || ldc < N || lda % 8 || ldc % 8 || (!w_packed && (ldw < K || ldw % 8))) return SSAM_EINVAL;
     if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
     if (N % 128 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
     if (tile < 0 || tile > 4) return SSAM_EINVAL;
+    if (w_packed && (tile == 2 || tile == 4)) return SSAM_EUNSUPPORTED;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
     if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD) {
         if (!row_map || rows_per_batch <= 0 || map_batch_stride < 0 || dst_rows_per_batch <= 0) return SSAM_EINVAL;
@@ -155,7 +200,7 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, co
         return SSAM_EINVAL;
     }
     GemmLd ld = { lda, ldw, ldc };
-    return ssam_linear_impl(A, W, bias, C, M, N, K, ld, epilogue, rm, tile, workspace, workspace ? workspace_bytes : 0,
+    return ssam_linear_impl(A, W, bias, C, M, N, K, ld, w_packed != 0, epilogue, rm, tile, workspace, workspace ? workspace_bytes : 0,
                             (hipStream_t)stream);
 }
 
@@ -163,7 +208,7 @@ extern "C" int ssam_linear_tiled(const void *A, const void *W, const float *bias
                                  int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
                                  int dst_rows_per_batch, int tile, void *stream)
 {
-    return ssam_linear_ld(A, K, W, K, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
+    return ssam_linear_ld(A, K, W, K, 0, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
                           dst_rows_per_batch, tile, nullptr, 0, stream);
 }
 
@@ -171,6 +216,6 @@ extern "C" int ssam_linear(const void *A, const void *W, const float *bias, void
                            int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
                            int dst_rows_per_batch, void *stream)
 {
-    return ssam_linear_ld(A, K, W, K, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
+    return ssam_linear_ld(A, K, W, K, 0, bias, C, N, M, N, K, epilogue, row_map, rows_per_batch, map_batch_stride,
                           dst_rows_per_batch, 0, nullptr, 0, stream);
 }

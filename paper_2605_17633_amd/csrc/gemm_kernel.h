@@ -39,10 +39,10 @@ struct GemmRowMap {
 constexpr int GEMM_BK = 64;
 constexpr int GEMM_THREADS = 256;
 
-template <int BM, int BN, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int WGM = 2, int WGN = 2, bool WPACK = false>
 constexpr size_t gemm_lds_bytes()
 {
-    size_t pipe = (size_t)2 * (BM + BN) * GEMM_BK * sizeof(bf16);
+    size_t pipe = (size_t)2 * (BM + (WPACK ? 0 : BN)) * GEMM_BK * sizeof(bf16);
     size_t epi = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) + BM * sizeof(int);   // staging + scatter rows
     return pipe > epi ? pipe : epi;
 }
@@ -81,7 +81,7 @@ __device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t,
     n0 = (tn * sub_n + sub % sub_n) * bn;
 }
 
-template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                     bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
@@ -168,10 +168,89 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], bfr[slot_][j], acc[i][j], 0, 0, 0); \
     }
 
+    int buf = 0;
+    if (WPACK) {
+        // W arrives pre-shuffled into fragment order ([N/32][K/16][64 lanes][8]): every wave loads its own
+        // B fragments straight into registers with 1 KB coalesced loads, one slab ahead at k-step granularity
+        // (the fragments of k-step s of the next slab are requested as soon as this slab's step s has issued),
+        // and only A goes through LDS.
+        const int ksteps = K / 16;
+        const bf16 *wp = W + ((long)((n0 + wn) >> 5) * ksteps) * 512 + lane * 8;
+        bf16x8 wf[4][NT];
+#define GEMM_LOAD_W(kt_, ks_)                                                                         \
+        {                                                                                             \
+            _Pragma("unroll") for (int j = 0; j < NT; ++j)                                            \
+                wf[ks_][j] = *reinterpret_cast<const bf16x8 *>(wp + ((long)j * ksteps + (kt_) * 4 + (ks_)) * 512); \
+        }
+#define GEMM_LOAD_GLOBAL_A(kt_)                                                                       \
+        {                                                                                             \
+            _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                       \
+                ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + (kt_) * GEMM_BK);                    \
+        }
+#define GEMM_STORE_LDS_A(buf_)                                                                        \
+        {                                                                                             \
+            bf16 *as_ = As + (buf_) * BM * GEMM_BK + lst;                                             \
+            _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                       \
+                *reinterpret_cast<u32x4 *>(as_ + i * RSTEP * GEMM_BK) = ra[i];                        \
+        }
+#define GEMM_LOAD_AFRAGS(buf_, ks_, slot_)                                                            \
+        {                                                                                             \
+            const bf16 *as_ = As + (buf_) * BM * GEMM_BK + fa0 + ((((ks_) * 2 + half) ^ sw) << 3);    \
+            _Pragma("unroll") for (int i = 0; i < MT; ++i)                                            \
+                af[slot_][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * GEMM_BK);             \
+        }
+#define GEMM_MFMAS_W(slot_, ks_)                                                                      \
+        {                                                                                             \
+            _Pragma("unroll") for (int i = 0; i < MT; ++i)                                            \
+                _Pragma("unroll") for (int j = 0; j < NT; ++j)                                        \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], wf[ks_][j], acc[i][j], 0, 0, 0); \
+        }
+        GEMM_LOAD_GLOBAL_A(kb)
+        GEMM_LOAD_W(kb, 0) GEMM_LOAD_W(kb, 1) GEMM_LOAD_W(kb, 2) GEMM_LOAD_W(kb, 3)
+        GEMM_STORE_LDS_A(0)
+        LDS_BARRIER();
+        for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
+            GEMM_LOAD_AFRAGS(buf, 0, 0)
+            GEMM_LOAD_GLOBAL_A(kt + 1)
+            GEMM_LOAD_AFRAGS(buf, 1, 1)
+            GEMM_MFMAS_W(0, 0)
+            GEMM_LOAD_W(kt + 1, 0)
+            GEMM_LOAD_AFRAGS(buf, 2, 0)
+            GEMM_MFMAS_W(1, 1)
+            GEMM_LOAD_W(kt + 1, 1)
+            GEMM_LOAD_AFRAGS(buf, 3, 1)
+            GEMM_MFMAS_W(0, 2)
+            GEMM_LOAD_W(kt + 1, 2)
+            GEMM_MFMAS_W(1, 3)
+            GEMM_LOAD_W(kt + 1, 3)
+            GEMM_STORE_LDS_A(buf ^ 1)
+            GEMM_SGB(0x100, MT);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); }
+            GEMM_SGB(0x020, NT);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
+            GEMM_SGB(0x020, NT);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
+            GEMM_SGB(0x020, NT);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); }
+            GEMM_SGB(0x020, NT);
+            LDS_BARRIER();
+        }
+        GEMM_LOAD_AFRAGS(buf, 0, 0)
+        GEMM_LOAD_AFRAGS(buf, 1, 1)
+        GEMM_MFMAS_W(0, 0)
+        GEMM_LOAD_AFRAGS(buf, 2, 0)
+        GEMM_MFMAS_W(1, 1)
+        GEMM_LOAD_AFRAGS(buf, 3, 1)
+        GEMM_MFMAS_W(0, 2)
+        GEMM_MFMAS_W(1, 3)
+    } else {
     GEMM_LOAD_GLOBAL(kb)
     GEMM_STORE_LDS(0)
     LDS_BARRIER();
-    int buf = 0;
     for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
         GEMM_LOAD_FRAGS(buf, 0, 0)
         GEMM_LOAD_GLOBAL(kt + 1)
@@ -207,6 +286,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         GEMM_LOAD_FRAGS(buf, 3, 1)
         GEMM_MFMAS(0)
         GEMM_MFMAS(1)
+    }
     }
 
     // ---- epilogue: 32-row slices through a per-wave fp32 LDS region

@@ -85,9 +85,12 @@ def test_vit_h_encoder_full_depth():
     torch.cuda.synchronize()
     got_all = to_np(xd)
     assert np.isfinite(got_all).all()
-    # determinism: a second run on the same input gives the same bits
+    # determinism: a second run on the same input gives the same bits, also with the Linear weights in
+    # MFMA fragment order (the form bench.py times)
     xd2 = torch.from_numpy(x.reshape(BATCH, n, SHAPE.D)).to(DEV).to(torch.bfloat16).contiguous()
-    B.ssam_encoder_forward(xd2, structs, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf)
+    wps = [B.pack_block_weights(w) for w in wds]                    # kept alive: the structs hold raw pointers
+    packed = [B.block_weights_struct(w) for w in wps]
+    B.ssam_encoder_forward(xd2, packed, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf)
     torch.cuda.synchronize()
     assert torch.equal(xd, xd2)
     keep_gpu = keep[0].cpu().numpy()

@@ -200,6 +200,40 @@ def test_linear_tail_cut_along_k(tile, M, N, epi):
     assert_close(to_np(out), to_np(plain).astype(np.float64), "K-split against one-pass tail", tol=1e-2)
 
 
+@pytest.mark.parametrize("tile,M,N,K,epi", [(1, 700, 512, 192, 0), (3, 333, 384, 64, 1), (0, 8400, 2048, 2048, 0),
+                                            (1, 8400, 2048, 128, 2), (3, 4200, 2048, 2048, 0)])
+def test_linear_packed_weights(tile, M, N, K, epi):
+    """Weights in MFMA fragment order (ssam_pack_weight): same bits as the row-major form, on the plain,
+    left-over and K-split launches and with every epilogue."""
+    announce("linear packed", tile, M, N, K, epi)
+    rng = np.random.default_rng(18)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    Ad, Wd, bd = dev_bf16(A), dev_bf16(W), dev_f32(b)
+    Wp = B.ssam_pack_weight(Wd)
+    # the packing itself, against its definition
+    ref_p = to_np(Wd).reshape(N // 32, 32, K // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(N, K)
+    assert np.array_equal(to_np(Wp), ref_p)
+    ws = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    kw = {}
+    if epi == 2:
+        rows = np.sort(rng.permutation(M + 9)[:M]).astype(np.int32)
+        kw = dict(row_map=dev_i32(rows), rows_per_batch=M, map_batch_stride=0, dst_rows_per_batch=M + 9)
+        x = inputs.bf16_round(rng.normal(size=(M + 9, N)).astype(np.float32))
+        o1, o2 = dev_bf16(x), dev_bf16(x)
+    else:
+        o1 = o2 = None
+    o1 = B.ssam_linear_ld(Ad, Wd, bd, o1, epilogue=epi, tile=tile, workspace=ws, **kw)
+    o2 = B.ssam_linear_ld(Ad, Wp, bd, o2, epilogue=epi, tile=tile, workspace=ws, w_packed=True, **kw)
+    assert torch.equal(o1, o2)
+    if epi == 0:
+        assert_close(to_np(o2), _gemm_ref(A, W, b), "packed linear", tol=1e-2)
+    with pytest.raises(B.SsamError) as e:
+        B.ssam_linear_ld(Ad, Wp, bd, epilogue=0, tile=2, w_packed=True)
+    assert e.value.code == B.EUNSUPPORTED
+
+
 def test_linear_row_strides():
     """Operands and result as column slices of wider buffers: strides are honoured, padding untouched."""
     announce("linear strides")
