@@ -74,6 +74,39 @@ def grid_sigma(w: int, G: int):
     return stripe_sort(morton_order(w, w), G)
 
 
+def content_order(scores, G: int):
+    """Content-aware order of one attention group (Sec. 4.1): cells ranked by score descending
+    (ties: lower index), then the stripe interleave.  Returns (sigma, sigma_inv)."""
+    sc = _f32(scores).reshape(-1)
+    n = sc.size
+    sigma = np.empty(n, np.int32)
+    sinv = np.empty(n, np.int32)
+    _check(lib().oracle_content_order(_p(sc), C.c_int(n), C.c_int(G), _p(sigma), _p(sinv)), "oracle_content_order")
+    return sigma, sinv
+
+
+def content_tables(scores, g: int, ws: int, G: int):
+    """Per-image tables of the content-aware order: for every window (ws = 0: the whole grid) the
+    scan position -> spatial index gather table (-1 = padding) and scan position -> cell-in-window
+    sigma.  scores [g,g] of one image.  Returns (table [nW*S], sigma [nW,S])."""
+    sc = _f32(scores).reshape(g, g)
+    w = ws if ws > 0 else g
+    nws = -(-g // w)
+    S = w * w
+    table = np.empty((nws * nws, S), np.int32)
+    sig = np.empty((nws * nws, S), np.int32)
+    for wr in range(nws):
+        for wc in range(nws):
+            ms = np.full((w, w), -np.inf, np.float32)
+            rows, cols = min(w, g - wr * w), min(w, g - wc * w)
+            ms[:rows, :cols] = sc[wr * w:wr * w + rows, wc * w:wc * w + cols]
+            sigma, _ = content_order(ms, G)
+            row, col = wr * w + sigma // w, wc * w + sigma % w
+            sig[wr * nws + wc] = sigma
+            table[wr * nws + wc] = np.where((row < g) & (col < g), row * g + col, -1)
+    return table.reshape(-1), sig
+
+
 def window_table(g: int, ws: int, G: int) -> np.ndarray:
     nws = (g + ws - 1) // ws
     t = np.empty(nws * nws * ws * ws, np.int32)
@@ -168,8 +201,10 @@ class BlockWeights:
     b2: np.ndarray
 
 
-def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: float = 1e-6) -> np.ndarray:
-    """x [g,g,D] one image; ws = 0 for a global block.  Returns the block output."""
+def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: float = 1e-6,
+                  order_scores=None) -> np.ndarray:
+    """x [g,g,D] one image; ws = 0 for a global block.  order_scores [g,g]: rank every attention
+    group's tokens by these scores (content-aware order) instead of by position.  Returns the block output."""
     x = _f32(x).copy()
     g, g2, D = x.shape
     assert g == g2
@@ -179,9 +214,11 @@ def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: 
     w = ws if ws > 0 else g
     d = D // h
     assert a["rel_h"].shape == (2 * w - 1, d), (a["rel_h"].shape, w, d)
+    osc = np.ascontiguousarray(_f32(order_scores).reshape(g, g)) if order_scores is not None else None
     rc = lib().oracle_encoder_block(
         _p(x), C.c_int(g), C.c_int(D), C.c_int(h), C.c_int(Dm), C.c_int(ws), C.c_int(G), C.c_int(Bm),
         C.c_double(r), _p(keep), C.c_int(keep.size), C.c_double(eps),
+        _p(osc),
         _p(a["ln1_g"]), _p(a["ln1_b"]), _p(a["wqkv"]), _p(a["bqkv"]), _p(a["rel_h"]), _p(a["rel_w"]),
         _p(a["wproj"]), _p(a["bproj"]), _p(a["ln2_g"]), _p(a["ln2_b"]),
         _p(a["w1"]), _p(a["b1"]), _p(a["w2"]), _p(a["b2"]))
@@ -190,15 +227,16 @@ def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: 
 
 
 def encoder(x, blocks, h: int, ws: int, global_blocks, G: int, r: float, rho: float,
-            Bm_window: int = 32, Bm_global: int = 128, eps: float = 1e-6):
+            Bm_window: int = 32, Bm_global: int = 128, eps: float = 1e-6, content_order: bool = False):
     """One image through a stack of blocks (Sec. 4: scores and keep-set are taken
     once, from the encoder input, and reused by every block).  Returns (y, keep)."""
     x = _f32(x)
     g = x.shape[0]
     K = keep_count(g * g, rho)
-    keep = select_tokens(score_tokens(x), K)
+    scores = score_tokens(x)
+    keep = select_tokens(scores, K)
     for i, wt in enumerate(blocks):
         is_global = i in global_blocks
         x = encoder_block(x, wt, h, 0 if is_global else ws, G, Bm_global if is_global else Bm_window,
-                          r, keep, eps)
+                          r, keep, eps, order_scores=scores if content_order else None)
     return x, keep

@@ -24,7 +24,11 @@
  * mask tile counts; attention against library softmax attention at r = 1 and
  * brute force on tiny inputs; Sobel against library correlation and the ramp
  * closed form; top-k against a full sort; MLP against a library MLP at rho = 1;
- * the block at r = rho = 1 against a library-built dense SAM block.
+ * the block at r = rho = 1 against a library-built dense SAM block; the
+ * content-aware order against a hand-derived example, a library sort with the
+ * paper's transpose, its rank structure, and two properties of the block that
+ * uses it (order irrelevant at r = 1; scores decreasing along the Z-order
+ * reproduce the position-only block).
  * The paper prints no worked numeric example of the block: whole-block values
  * at r < 1 are "parity unpinned" by the paper itself and rest on the pins of
  * the parts.
@@ -106,6 +110,40 @@ static int grid_sigma(int w, int G, int32_t *sigma, int32_t *sigma_inv)
     if (rc == 0) rc = oracle_stripe_sort(pi, n, G, sigma, sigma_inv);
     free(pi);
     return rc;
+}
+
+/* Content-aware order of one attention group (Sec. 4.1, "Gradient-Based
+ * Ordering" + "Stripe-Sort Permutation"): pi = the group's cells sorted by
+ * score M descending (equal scores: lower cell index first; NaN counts as
+ * -inf), sigma = stripe_G(pi).  Cells that are window padding are passed with
+ * score -INFINITY and therefore rank last. */
+typedef struct { float m; int32_t cell; } ranked_cell;
+
+static int cmp_ranked_cell(const void *a, const void *b)
+{
+    const ranked_cell *x = (const ranked_cell *)a, *y = (const ranked_cell *)b;
+    if (x->m > y->m) return -1;
+    if (x->m < y->m) return 1;
+    return (x->cell > y->cell) - (x->cell < y->cell);
+}
+
+int oracle_content_order(const float *scores, int n, int G, int32_t *sigma, int32_t *sigma_inv)
+{
+    if (!scores || !sigma || n <= 0 || G <= 0 || n % G != 0) return ORACLE_EINVAL;
+    ranked_cell *rc = (ranked_cell *)malloc((size_t)n * sizeof(ranked_cell));
+    int32_t *pi = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    if (!rc || !pi) { free(rc); free(pi); return ORACLE_ENOMEM; }
+    for (int i = 0; i < n; ++i) {
+        float m = scores[i];
+        if (m != m) m = -INFINITY;
+        if (m == 0.0f) m = 0.0f;                  /* -0.0 ranks as +0.0 */
+        rc[i].m = m; rc[i].cell = i;
+    }
+    qsort(rc, (size_t)n, sizeof(ranked_cell), cmp_ranked_cell);
+    for (int i = 0; i < n; ++i) pi[i] = rc[i].cell;
+    int r = oracle_stripe_sort(pi, n, G, sigma, sigma_inv);
+    free(rc); free(pi);
+    return r;
 }
 
 /* Window-major gather table (App. A.1, "window-major -> spatial perms"; SAM's
@@ -398,7 +436,7 @@ int oracle_routed_mlp(float *x, int n, int D, int Dm, const int32_t *keep, int K
 /*   routed MLP over the keep-set.  qkv output channel = which*D + head*d + c*/
 /* ------------------------------------------------------------------------ */
 int oracle_encoder_block(float *x, int g, int D, int h, int Dm, int ws, int G, int Bm,
-                         double r, const int32_t *keep, int K, double eps,
+                         double r, const int32_t *keep, int K, double eps, const float *order_scores,
                          const float *ln1_g, const float *ln1_b,
                          const float *wqkv, const float *bqkv,
                          const float *rel_h, const float *rel_w,
@@ -449,7 +487,22 @@ int oracle_encoder_block(float *x, int g, int D, int h, int Dm, int ws, int G, i
                         kh[dst] = (float)qkv[(size_t)s * 3 * D + 1 * D + head * d + c];
                         vh[dst] = (float)qkv[(size_t)s * 3 * D + 2 * D + head * d + c];
                     }
-            rc = oracle_attention(qh, kh, vh, rel_h, rel_w, h, w, d, G, Bm, r, oh);
+            if (order_scores) {
+                /* content-aware order of this group: its cells ranked by the image's score map */
+                float *ms = (float *)malloc((size_t)S * sizeof(float));
+                int32_t *sg = (int32_t *)malloc((size_t)S * sizeof(int32_t));
+                int32_t *si = (int32_t *)malloc((size_t)S * sizeof(int32_t));
+                if (!ms || !sg || !si) { free(ms); free(sg); free(si); rc = ORACLE_ENOMEM; break; }
+                for (int s = 0; s < S; ++s) {
+                    int row = wr * w + s / w, col = wc * w + s % w;
+                    ms[s] = (row < g && col < g) ? order_scores[(size_t)row * g + col] : -INFINITY;
+                }
+                rc = oracle_content_order(ms, S, G, sg, si);
+                if (rc == 0) rc = oracle_attention_ordered(qh, kh, vh, rel_h, rel_w, h, w, d, si, Bm, r, oh);
+                free(ms); free(sg); free(si);
+            } else {
+                rc = oracle_attention(qh, kh, vh, rel_h, rel_w, h, w, d, G, Bm, r, oh);
+            }
             if (rc) break;
             /* concat heads, output projection, residual; padded cells dropped */
 #pragma omp parallel for schedule(static)
