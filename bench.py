@@ -13,7 +13,8 @@ Extra legs (run after the timed region, reported inside the same JSON line):
   parts         the other entry points of the path timed one by one with HIP
                 events (attention, routed MLP, LN+gather, scores, selection),
                 each against the roofline that bounds it
-  dense, density_0.3   the same kernels at density 1.0 (the "dense GPU block") and 0.3
+  dense, density_0.3, content_order   the same kernels at density 1.0 (the "dense GPU block"), at 0.3,
+                and at 0.4 with the content-aware order of Sec. 4.1 (per-image tables)
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -349,6 +350,27 @@ def main():
         d_ms = ddt / dsteps * 1e3
         out["dense"] = {"ms_per_step": round(d_ms, 3), "images_per_s": round(Bn * dsteps / ddt, 3),
                         "speedup_sparse_over_dense": round(d_ms / ms_per_step, 3)}
+        # content-aware Stripe-Sort order (Sec. 4.1): per-image tables built from the scores inside the step
+        nW_, S_ = (-(-g // shape.ws)) ** 2, shape.ws ** 2
+        cl_c = B.make_cfg(Bn, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r, content_order=True)
+        cg_c = B.make_cfg(Bn, g, shape.D, shape.heads, shape.Dm, 0, 128, K, r, content_order=True)
+        ctab = [torch.empty((Bn, nW_ * S_), dtype=torch.int32, device=dev), torch.empty((Bn * nW_, S_), dtype=torch.int32, device=dev),
+                torch.empty((Bn, n), dtype=torch.int32, device=dev), torch.empty((Bn, n), dtype=torch.int32, device=dev)]
+
+        def step_content():
+            x.copy_(x0)
+            B.ssam_encoder_forward(x, structs, flags, cl_c, cg_c, ctab[0], ctab[1], ctab[2], ctab[3], scores, keep, ws_buf, plan=plan)
+
+        for _ in range(2):
+            step_content()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(dsteps):
+            step_content()
+        torch.cuda.synchronize()
+        cdt = time.perf_counter() - t0
+        out["content_order"] = {"ms_per_step": round(cdt / dsteps * 1e3, 3), "images_per_s": round(Bn * dsteps / cdt, 3),
+                                "note": "tokens of every window / image ranked by the Sobel score, tables rebuilt every step"}
         if abs(r - 0.3) > 1e-9:
             K3 = B.ssam_keep_count(n, 0.3)
             cfg_l3, cfg_g3 = make_cfgs(0.3, K3)

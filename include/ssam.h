@@ -99,6 +99,19 @@ int ssam_ln_gather(const void *x, const int32_t *idx, int idx_batch_stride,
                    const float *gamma, const float *beta, float eps, void *y,
                    int B, int Nin, int Nout, int D, void *stream);
 
+/* Content-aware Stripe-Sort order (Sec. 4.1, "Gradient-Based Ordering" and
+ * "Stripe-Sort Permutation"): per image and per attention group (a ws x ws
+ * window of the grid padded to a multiple of ws, or the whole grid when ws = 0)
+ * the group's cells are ranked by score descending (equal scores: lower cell
+ * first; NaN as -inf, -0 as +0; padding cells last), pi = that ranking,
+ * sigma[t'*(S/G) + t] = pi[t*G + t'].  scores dev fp32 [B][g*g] (Eq. 1).
+ * Outputs, dev int32, S = w*w, nW groups per image:
+ *   gather_table [B][nW*S]: scan slot -> spatial index row*g+col, -1 = padding
+ *   sigma        [B*nW][S]: scan position -> cell of the group (row*w+col)
+ * S % G == 0 (else SSAM_EINVAL), w <= 128 (else SSAM_EUNSUPPORTED). */
+int ssam_build_content_tables(const float *scores, int B, int g, int ws, int G,
+                              int32_t *gather_table, int32_t *sigma, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Dense contraction (the block's qkv / proj / fc1 / fc2 layers)             */
 /* ------------------------------------------------------------------------- */
@@ -173,13 +186,17 @@ int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *strea
  * spatial cell of the w x w grid, S = w*w.
  *   q, k, v  dev bf16; element (g, p, head, c) at ptr[(g*S+p)*row_stride + head*d + c]
  *            (a packed [groups][S][3][h][d] buffer: row_stride = 3*h*d, k = q + h*d, v = q + 2*h*d)
- *   rel_h, rel_w  dev bf16 [(2w-1)][d]      sigma  dev int32 [S]
+ *   rel_h, rel_w  dev bf16 [(2w-1)][d]
+ *   sigma    dev int32: sigma_group_stride = 0: one table [S] shared by all groups (the
+ *            position-only order); otherwise group g reads sigma + g*sigma_group_stride
+ *            (>= S; the per-image, per-window tables of ssam_build_content_tables)
  *   out      dev bf16 [groups][S][h*d]
  * Built for d in {64, 80} (d % 16 == 0, d <= 96 accepted), mask_block = 32 with
  * S <= 224 (windows) and mask_block = 128 with S <= 16384 (global); otherwise
  * SSAM_EUNSUPPORTED. */
 int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,
-                          const void *rel_h, const void *rel_w, const int32_t *sigma, void *out,
+                          const void *rel_h, const void *rel_w, const int32_t *sigma,
+                          long sigma_group_stride, void *out,
                           int groups, int S, int w, int h, int d, int mask_block, double r,
                           float scale, void *stream);
 
@@ -238,6 +255,10 @@ typedef struct ssam_block_cfg {
     int K;            /* kept tokens per image for the routed MLP                */
     double r;         /* attention density in (0,1]                              */
     float eps;        /* LayerNorm epsilon                                       */
+    int content_order;/* 0: position-only order, tables shared by all images;
+                         1: content-aware order, per-image tables (see below)    */
+    int stripe;       /* G of the stripe interleave when content_order != 0 (the
+                         paper's 4 x 4 mosaic: 4); ignored otherwise            */
 } ssam_block_cfg;
 
 /* One structured-sparse block, in place on x dev bf16 [B][g][g][D]:
@@ -247,6 +268,8 @@ typedef struct ssam_block_cfg {
  * gather_table dev int32: ws > 0: ssam_build_window_table(g, ws, G) (nws*nws*ws*ws);
  *                         ws = 0: ssam_build_perm(g, g, G) (g*g).
  * sigma dev int32 [S]: ssam_build_perm(w, w, G) of one attention group.
+ * With cfg->content_order != 0 both tables are the per-image outputs of
+ * ssam_build_content_tables: gather_table [B][nW*S], sigma [B*nW][S].
  * keep_idx dev int32 [B][K].  workspace >= ssam_encoder_block_workspace_bytes(cfg). */
 size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg);
 int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
@@ -258,7 +281,10 @@ int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cf
  * keep-set are taken from the input x, then block i runs with cfg_local or,
  * where is_global[i] != 0, cfg_global.  weights, is_global: host arrays of
  * n_blocks entries.  keep_idx dev int32 [B][K] is written and then read;
- * scores dev fp32 [B][N] likewise.  Tables as for ssam_encoder_block.
+ * scores dev fp32 [B][N] likewise.  Tables as for ssam_encoder_block; with
+ * content_order set in the cfgs (both or neither) the four table arguments are
+ * per-image buffers that this call FILLS from the scores (Sec. 4.1: the order is
+ * computed once, in the first layer) before the first block reads them.
  * workspace >= ssam_encoder_workspace_bytes(cfg_local, cfg_global).
  * qkv_events: optional instrumentation, host array of 2*n_blocks hipEvent_t
  * (NULL = none): events [2i] and [2i+1] are recorded on the stream right before
@@ -267,8 +293,8 @@ int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cf
 size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global);
 int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
                          const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,
-                         const int32_t *window_table, const int32_t *sigma_window,
-                         const int32_t *global_table, const int32_t *sigma_global,
+                         int32_t *window_table, int32_t *sigma_window,
+                         int32_t *global_table, int32_t *sigma_global,
                          float *scores, int32_t *keep_idx,
                          void *workspace, size_t workspace_bytes, void **qkv_events, void *stream);
 

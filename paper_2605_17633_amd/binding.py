@@ -37,7 +37,8 @@ class BlockWeights(C.Structure):
 
 class BlockCfg(C.Structure):
     _fields_ = [("B", C.c_int), ("g", C.c_int), ("D", C.c_int), ("heads", C.c_int), ("Dm", C.c_int),
-                ("ws", C.c_int), ("mask_block", C.c_int), ("K", C.c_int), ("r", C.c_double), ("eps", C.c_float)]
+                ("ws", C.c_int), ("mask_block", C.c_int), ("K", C.c_int), ("r", C.c_double), ("eps", C.c_float),
+                ("content_order", C.c_int), ("stripe", C.c_int)]
 
 
 def lib():
@@ -153,6 +154,21 @@ def ssam_ln_gather(x, idx, idx_batch_stride, gamma, beta, eps, Nout, y=None):
     return y
 
 
+def ssam_build_content_tables(scores, g, ws, G=4, gather_table=None, sigma=None):
+    """scores [B, g*g] fp32 -> (gather_table [B, nW*S], sigma [B*nW, S]) of the content-aware order."""
+    Bn = scores.shape[0]
+    w = ws if ws > 0 else g
+    nW, S = (-(-g // w)) ** 2, w * w
+    if gather_table is None:
+        gather_table = torch.empty((Bn, nW * S), dtype=torch.int32, device=scores.device)
+    if sigma is None:
+        sigma = torch.empty((Bn * nW, S), dtype=torch.int32, device=scores.device)
+    _check("ssam_build_content_tables", lib().ssam_build_content_tables(
+        _f32(scores, "scores"), C.c_int(Bn), C.c_int(g), C.c_int(ws), C.c_int(G),
+        _i32(gather_table, "gather_table"), _i32(sigma, "sigma"), _stream()))
+    return gather_table, sigma
+
+
 # ------------------------------------------------------------------ GEMM
 def ssam_linear(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows_per_batch=1, map_batch_stride=0,
                 dst_rows_per_batch=1, tile=0):
@@ -199,7 +215,7 @@ def ssam_linear_ld(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows
 
 # ------------------------------------------------------------------ attention
 def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None, out=None):
-    """qkv: packed [groups, S, 3, h, d] bf16.  Returns [groups, S, h*d]."""
+    """qkv: packed [groups, S, 3, h, d] bf16; sigma [S] shared, or [groups, S] per group.  Returns [groups, S, h*d]."""
     groups, S, three, h, d = qkv.shape
     assert three == 3
     if out is None:
@@ -211,7 +227,8 @@ def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None
     esz = 2
     _check("ssam_sparse_attention", lib().ssam_sparse_attention(
         C.c_void_p(base), C.c_void_p(base + h * d * esz), C.c_void_p(base + 2 * h * d * esz), C.c_long(3 * h * d),
-        _bf(rel_h, "rel_h"), _bf(rel_w, "rel_w"), _i32(sigma, "sigma"), _bf(out, "out"),
+        _bf(rel_h, "rel_h"), _bf(rel_w, "rel_w"), _i32(sigma, "sigma"), C.c_long(S if sigma.dim() == 2 else 0),
+        _bf(out, "out"),
         C.c_int(groups), C.c_int(S), C.c_int(w), C.c_int(h), C.c_int(d), C.c_int(mask_block), C.c_double(r),
         C.c_float(scale), _stream()))
     return out
@@ -304,8 +321,8 @@ def block_weights_struct(wt: dict) -> BlockWeights:
     return s
 
 
-def make_cfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps=1e-6) -> BlockCfg:
-    return BlockCfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps)
+def make_cfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps=1e-6, content_order=False, stripe=4) -> BlockCfg:
+    return BlockCfg(B, g, D, heads, Dm, ws, mask_block, K, r, eps, 1 if content_order else 0, stripe)
 
 
 def ssam_encoder_block_workspace_bytes(cfg: BlockCfg) -> int:

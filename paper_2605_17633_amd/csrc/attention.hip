@@ -41,6 +41,7 @@ struct AttnParams {
     long row_stride;
     const bf16 *rel_h, *rel_w;
     const int32_t *sigma;
+    long sigma_stride;      // elements between the sigma tables of consecutive groups; 0 = one shared table
     bf16 *out;
     int S, w, h, n_pre;
     float scale_log2e;
@@ -311,7 +312,8 @@ attn_window_kernel(AttnParams P, int n_groups)
     const int nloads = (SP * C::CH + blockDim.x - 1) / blockDim.x;     // <= WIN_MAX_LOADS (checked on the host)
 
     // problem-independent state: scan-order geometry and the rel-pos tables
-    for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(P.sigma, p, S, P.w, ts);
+    if (P.sigma_stride == 0)
+        for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(P.sigma, p, S, P.w, ts);
     for (int id = tid; id < 2 * rrows * C::CH; id += blockDim.x) {
         int tab = id / (rrows * C::CH), rem = id % (rrows * C::CH), row = rem / C::CH, c = rem % C::CH;
         u32x4 v = { 0, 0, 0, 0 };
@@ -320,7 +322,7 @@ attn_window_kernel(AttnParams P, int n_groups)
     }
     const int q0 = wave * 32, qpos = q0 + l32;
     const int qclamp = qpos < S ? qpos : S - 1;
-    const uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
+    uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
     float *tq = reinterpret_cast<float *>(T + wave * wsb);
     const int nact = P.n_pre + (wave >= P.n_pre ? 1 : 0);
 
@@ -361,6 +363,11 @@ attn_window_kernel(AttnParams P, int n_groups)
                 *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = rk[i];
                 *reinterpret_cast<u32x4 *>(Vs + key * C::KSTR + c * 8) = rv[i];
             }
+        }
+        if (P.sigma_stride != 0) {                // per-group order: this window's own sigma
+            const int32_t *sg = P.sigma + (long)grp * P.sigma_stride;
+            for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(sg, p, S, P.w, ts);
+            qrc = key_row_col(sg, qclamp, S, P.w);
         }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) qf[ks] = qnext[ks];
@@ -436,7 +443,8 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
     const int qclamp = qpos < S ? qpos : S - 1;
     bf16x8 qf[C::KS];
     load_q_frags<D>(qf, P.q + base + (long)qclamp * P.row_stride);
-    const uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
+    const int32_t *sg = P.sigma + (long)grp * P.sigma_stride;
+    const uint32_t qrc = key_row_col(sg, qclamp, S, P.w);
     GlbTab *tq = reinterpret_cast<GlbTab *>(Tb + wave * wsb);
 
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
@@ -453,7 +461,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8);    \
             rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8);    \
         }                                                                                               \
-        if (tid < GLB_TILE) rrc = key_bias_offsets(P.sigma, key0_ + tid, S, P.w, ts, sizeof(GlbTab));   \
+        if (tid < GLB_TILE) rrc = key_bias_offsets(sg, key0_ + tid, S, P.w, ts, sizeof(GlbTab));        \
     }
 #define ATTN_STORE_TILE()                                                                               \
     {                                                                                                   \
@@ -532,12 +540,14 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
 }  // namespace
 
 extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,
-                                     const void *rel_h, const void *rel_w, const int32_t *sigma, void *out,
+                                     const void *rel_h, const void *rel_w, const int32_t *sigma,
+                                     long sigma_group_stride, void *out,
                                      int groups, int S, int w, int h, int d, int mask_block, double r,
                                      float scale, void *stream)
 {
     if (!q || !k || !v || !rel_h || !rel_w || !sigma || !out) return SSAM_EINVAL;
     if (groups <= 0 || S <= 0 || w <= 0 || h <= 0 || d <= 0 || !(r > 0.0) || r > 1.0) return SSAM_EINVAL;
+    if (sigma_group_stride != 0 && sigma_group_stride < S) return SSAM_EINVAL;
     if (w * w != S || row_stride < (long)h * d || row_stride % 8 != 0) return SSAM_EINVAL;
     if (!ssam_aligned16(q) || !ssam_aligned16(k) || !ssam_aligned16(v) || !ssam_aligned16(rel_h) ||
         !ssam_aligned16(rel_w) || !ssam_aligned16(out))
@@ -555,6 +565,7 @@ extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v
     P.row_stride = row_stride;
     P.rel_h = (const bf16 *)rel_h; P.rel_w = (const bf16 *)rel_w;
     P.sigma = sigma;
+    P.sigma_stride = sigma_group_stride;
     P.out = (bf16 *)out;
     P.S = S; P.w = w; P.h = h;
     P.n_pre = ssam_prefix_tiles(ssam_div_up(S, mask_block), r);

@@ -107,7 +107,8 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     void *qkv = ws + align256((size_t)rows * D * 2);
     hipStream_t st = (hipStream_t)stream;
 
-    int rc = ssam_ln_gather(x, gather_table, 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
+    const int per_image = cfg->content_order != 0;             // tables carry a leading [B] dimension
+    int rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
@@ -115,11 +116,11 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (rc != SSAM_OK) return rc;
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
-    rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, u,
+    rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u,
                                B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
                                1.0f / sqrtf((float)g.d), stream);
     if (rc != SSAM_OK) return rc;
-    GemmRowMap back = { gather_table, g.Nout, 0, g.N };
+    GemmRowMap back = { gather_table, g.Nout, per_image ? g.Nout : 0, g.N };
     rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, w->packed != 0, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, nullptr, 0, st);
     if (rc != SSAM_OK) return rc;
     return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, w->packed != 0,
@@ -145,8 +146,8 @@ extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, 
 
 extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
                                     const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,
-                                    const int32_t *window_table, const int32_t *sigma_window,
-                                    const int32_t *global_table, const int32_t *sigma_global,
+                                    int32_t *window_table, int32_t *sigma_window,
+                                    int32_t *global_table, int32_t *sigma_global,
                                     float *scores, int32_t *keep_idx,
                                     void *workspace, size_t workspace_bytes, void **qkv_events, void *stream)
 {
@@ -163,8 +164,21 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
         return SSAM_EINVAL;
     if (workspace_bytes < ssam_encoder_workspace_bytes(any_local ? cfg_local : nullptr, any_global ? cfg_global : nullptr))
         return SSAM_EWORKSPACE;
+    if (any_local && any_global && (cfg_local->content_order != 0) != (cfg_global->content_order != 0)) return SSAM_EINVAL;
     int rc = ssam_score_tokens(x, scores, c0->B, c0->g, c0->g, c0->D, workspace, workspace_bytes, stream);
     if (rc != SSAM_OK) return rc;
+    if (c0->content_order != 0) {                 // Sec. 4.1: the content-aware order is taken once, from these scores
+        const int G = c0->stripe;
+        if (G <= 0) return SSAM_EINVAL;
+        if (any_local) {
+            rc = ssam_build_content_tables(scores, c0->B, c0->g, cfg_local->ws, G, window_table, sigma_window, stream);
+            if (rc != SSAM_OK) return rc;
+        }
+        if (any_global) {
+            rc = ssam_build_content_tables(scores, c0->B, c0->g, cfg_global->ws, G, global_table, sigma_global, stream);
+            if (rc != SSAM_OK) return rc;
+        }
+    }
     rc = ssam_select_tokens(scores, keep_idx, c0->B, c0->g * c0->g, c0->K, stream);
     if (rc != SSAM_OK) return rc;
     for (int i = 0; i < n_blocks; ++i) {

@@ -258,6 +258,53 @@ static int mover_grid(long total_chunks)
     return (int)(blocks < 1 ? 1 : (blocks > 256L * 32 ? 256L * 32 : blocks));
 }
 
+// ---------------------------------------------------------------- content-aware order
+// One workgroup per (image, window): the window's cells are ranked by (score descending, cell index
+// ascending; padding cells last) with a bitonic sort of 64-bit keys in LDS, then the stripe interleave
+// sigma[g*(S/G)+t] = pi[t*G+g] (Sec. 4.1) places rank t*G+g at scan position g*(S/G)+t.
+// P = the power of two >= S that is sorted; entries S..P-1 carry the largest key.
+__global__ void __launch_bounds__(1024)
+content_tables_kernel(const float *__restrict__ scores, int g, int w, int nws, int G, int P,
+                      int32_t *__restrict__ gather_table, int32_t *__restrict__ sigma)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
+    const int S = w * w, nW = nws * nws;
+    const int b = blockIdx.x / nW, win = blockIdx.x % nW;
+    const int wr = win / nws, wc = win % nws;
+    const float *sc = scores + (long)b * g * g;
+    for (int i = threadIdx.x; i < P; i += blockDim.x) {
+        unsigned long long key = ~0ull;
+        if (i < S) {
+            const int row = wr * w + i / w, col = wc * w + i % w;
+            const float m = (row < g && col < g) ? sc[row * g + col] : -INFINITY;
+            key = ((unsigned long long)(~score_key(m)) << 32) | (unsigned)i;
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < P / 2; t += blockDim.x) {
+                const int i = 2 * t - (t & (j - 1));            // index with bit j clear
+                const int p = i | j;
+                const unsigned long long a = keys[i], c = keys[p];
+                const bool up = (i & k) == 0;
+                if ((a > c) == up) { keys[i] = c; keys[p] = a; }
+            }
+            __syncthreads();
+        }
+    const int rows = S / G;
+    for (int rk = threadIdx.x; rk < S; rk += blockDim.x) {
+        const int cell = (int)(keys[rk] & 0xffffffffu);
+        const int pos = (rk % G) * rows + rk / G;
+        const int row = wr * w + cell / w, col = wc * w + cell % w;
+        const long o = ((long)b * nW + win) * S + pos;
+        sigma[o] = cell;
+        gather_table[o] = (row < g && col < g) ? row * g + col : -1;
+    }
+}
+
 extern "C" int ssam_permute(const void *x, const int32_t *idx, void *y, int B, int Nin, int Nout, int D, void *stream)
 {
     if (!movers_args_ok(x, idx, y, B, Nin, Nout, D)) return SSAM_EINVAL;
@@ -332,6 +379,27 @@ extern "C" int ssam_select_tokens(const float *scores, int32_t *keep_idx, int B,
     if (!scores || !keep_idx || B <= 0 || N <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
     if (N > 65536) return SSAM_EUNSUPPORTED;
     hipLaunchKernelGGL(select_kernel, dim3(B), dim3(SEL_THREADS), 0, (hipStream_t)stream, scores, keep_idx, N, K);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_build_content_tables(const float *scores, int B, int g, int ws, int G,
+                                         int32_t *gather_table, int32_t *sigma, void *stream)
+{
+    if (!scores || !gather_table || !sigma || B <= 0 || g <= 0 || ws < 0 || G <= 0) return SSAM_EINVAL;
+    const int w = ws > 0 ? ws : g;
+    if (w > 128) return SSAM_EUNSUPPORTED;
+    const int S = w * w, nws = (g + w - 1) / w;
+    if (S % G != 0) return SSAM_EINVAL;
+    int P = 2;
+    while (P < S) P <<= 1;
+    const int threads = P / 2 < 1024 ? (P / 2 < 64 ? 64 : P / 2) : 1024;
+    const size_t lds = (size_t)P * sizeof(unsigned long long);
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(content_tables_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return SSAM_EHIP;
+    hipLaunchKernelGGL(content_tables_kernel, dim3(B * nws * nws), dim3(threads), lds, (hipStream_t)stream,
+                       scores, g, w, nws, G, P, gather_table, sigma);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }

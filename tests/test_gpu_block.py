@@ -240,3 +240,107 @@ def test_encoder_forward_small_stack():
                 y = oracle.encoder_block(y, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
                                          128 if glob else 32, r, keep_gpu[b])
             assert_close(got[b] - x[b], y - x[b], f"encoder stack b={b} (threshold tie)", stored=y, updates=6)
+
+
+# ------------------------------------------------------------------ content-aware order (Sec. 4.1)
+@pytest.mark.parametrize("B_,g,ws", [(2, 28, 14), (3, 64, 14), (2, 64, 0), (1, 16, 0), (2, 9, 4), (1, 128, 0)])
+def test_content_tables(B_, g, ws):
+    """Integer work, bit-exact: per-image, per-window ranking by score (ties to the lower cell,
+    padding last) and the stripe interleave, against the oracle."""
+    announce("content tables", B_, g, ws)
+    rng = np.random.default_rng(50 + g)
+    scores = inputs.lognormal_scores(rng, B_, g * g)
+    scores[:, rng.integers(0, g * g, g * g // 6)] = scores[:, :1]          # planted ties
+    scores[0, 3] = np.nan
+    scores[0, 5] = -0.0
+    scores[0, 6] = 0.0
+    table, sigma = B.ssam_build_content_tables(dev_f32(scores), g, ws)
+    table, sigma = table.cpu().numpy(), sigma.cpu().numpy()
+    w = ws if ws > 0 else g
+    nW = (-(-g // w)) ** 2
+    for b in range(B_):
+        t_ref, s_ref = oracle.content_tables(scores[b].reshape(g, g), g, ws, 4)
+        assert np.array_equal(table[b], t_ref)
+        assert np.array_equal(sigma[b * nW:(b + 1) * nW], s_ref)
+
+
+@pytest.mark.parametrize("ws,Bm,g", [(14, 32, 28), (0, 128, 32), (14, 32, 64)])
+def test_attention_with_per_group_order(ws, Bm, g):
+    """The attention kernels with one sigma table per group against the oracle with the same orders."""
+    announce("attention per-group sigma", ws, Bm, g)
+    rng = np.random.default_rng(60 + g)
+    h, d, B_ = 2, 80, 2
+    w = ws if ws > 0 else g
+    S, nW = w * w, (-(-g // w)) ** 2
+    scores = inputs.lognormal_scores(rng, B_, g * g)
+    _, sigma = B.ssam_build_content_tables(dev_f32(scores), g, ws)
+    groups = B_ * nW
+    q, k, v = (inputs.bf16_round(rng.normal(size=(groups, h, S, d)).astype(np.float32) * 0.7) for _ in range(3))
+    rel_h, rel_w = (inputs.bf16_round(rng.normal(size=(2 * w - 1, d)).astype(np.float32) * 0.3) for _ in range(2))
+    qkv = np.stack([q, k, v], axis=1).transpose(0, 3, 1, 2, 4)                 # [groups, S, 3, h, d] in SPATIAL order
+    sig = sigma.cpu().numpy()
+    qkv_scan = np.stack([qkv[gi][sig[gi]] for gi in range(groups)])            # rows gathered into scan order
+    out = B.ssam_sparse_attention(dev_bf16(qkv_scan), dev_bf16(rel_h), dev_bf16(rel_w), sigma, w, Bm, 0.4)
+    got = to_np(out).reshape(groups, S, h, d)
+    for gi in range(0, groups, max(1, groups // 5)):
+        sinv = np.empty(S, np.int32)
+        sinv[sig[gi]] = np.arange(S, dtype=np.int32)
+        ref = oracle.attention(q[gi], k[gi], v[gi], rel_h, rel_w, w, 4, Bm, 0.4, sinv=sinv)      # [h, S, d] spatial
+        assert_close(got[gi], ref.transpose(1, 0, 2)[sig[gi]], f"attention group {gi} own order")
+
+
+@pytest.mark.parametrize("depth,g", [(3, 28), (2, 64)])
+def test_encoder_stack_content_order(depth, g):
+    """ssam_encoder_forward with content_order: tables are built from the scores inside the call;
+    result against the oracle's encoder with the same option."""
+    announce("encoder content order", depth, g)
+    shape = inputs.ModelShape("vit_c", 256, depth, 4, 512, (depth - 1,), 14)
+    B_, r, rho = 2, 0.4, 0.4
+    n = g * g
+    wts = inputs.encoder_weights(70, shape, g)
+    for wt in wts:
+        for kname in ("wqkv", "rel_h", "rel_w"):
+            wt[kname] = inputs.bf16_round(wt[kname] * 4)               # peakier softmax: the mask matters
+    rng = np.random.default_rng(71)
+    x = inputs.token_field(rng, B_, g, shape.D)
+    K = oracle.keep_count(n, rho)
+    wds = [B.upload_block_weights(w, pack=(depth == 3)) for w in wts]
+    structs = [B.block_weights_struct(w) for w in wds]
+    flags = [i in shape.global_blocks for i in range(shape.depth)]
+    cfg_l = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r, content_order=True)
+    cfg_g = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, 0, 128, K, r, content_order=True)
+    nW = (-(-g // shape.ws)) ** 2
+    wtab = torch.empty((B_, nW * 196), dtype=torch.int32, device=DEV)
+    wsig = torch.empty((B_ * nW, 196), dtype=torch.int32, device=DEV)
+    gtab = torch.empty((B_, n), dtype=torch.int32, device=DEV)
+    gsig = torch.empty((B_, n), dtype=torch.int32, device=DEV)
+    xd = dev_bf16(x.reshape(B_, n, shape.D))
+    scores = torch.empty((B_, n), dtype=torch.float32, device=DEV)
+    keep = torch.empty((B_, K), dtype=torch.int32, device=DEV)
+    ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cfg_l, cfg_g), dtype=torch.uint8, device=DEV)
+    B.ssam_encoder_forward(xd, structs, flags, cfg_l, cfg_g, wtab, wsig, gtab, gsig, scores, keep, ws_buf)
+    torch.cuda.synchronize()
+    got = to_np(xd).reshape(x.shape)
+    sc_gpu = to_np(scores)
+    keep_gpu = keep.cpu().numpy()
+    for b in range(B_):
+        # the order is an integer decision on fp32 scores: both sides rank the SAME scores (the GPU's, which
+        # match the oracle's to 2e-5 relative: checked) so that near-ties cannot flip the order
+        sc_ref = oracle.score_tokens(x[b]).reshape(-1)
+        np.testing.assert_allclose(sc_gpu[b], sc_ref, rtol=2e-5, atol=2e-5 * sc_ref.max())
+        t_ref, s_ref = oracle.content_tables(sc_gpu[b].reshape(g, g), g, shape.ws, 4)
+        assert np.array_equal(wtab[b].cpu().numpy(), t_ref)
+        assert np.array_equal(wsig[b * nW:(b + 1) * nW].cpu().numpy(), s_ref)
+        y = x[b]
+        for i, w in enumerate(wts):
+            glob = i in shape.global_blocks
+            y = oracle.encoder_block(y, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
+                                     128 if glob else 32, r, keep_gpu[b], order_scores=sc_gpu[b].reshape(g, g))
+        assert_close(got[b] - x[b], y - x[b], f"content-order stack b={b}", stored=y, updates=2 * depth)
+        # and the content-aware result differs from the position-only one (the option is live)
+        z = x[b]
+        for i, w in enumerate(wts):
+            glob = i in shape.global_blocks
+            z = oracle.encoder_block(z, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
+                                     128 if glob else 32, r, keep_gpu[b])
+        assert np.abs(z - y).max() > 1e-3
