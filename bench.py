@@ -15,6 +15,7 @@ Extra legs (run after the timed region, reported inside the same JSON line):
                 each against the roofline that bounds it
   dense, density_0.3, content_order   the same kernels at density 1.0 (the "dense GPU block"), at 0.3,
                 and at 0.4 with the content-aware order of Sec. 4.1 (per-image tables)
+  other_models  SAM ViT-B and ViT-L shaped encoders at batch 1 (sparse and dense)
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -223,6 +224,52 @@ def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab,
     return parts
 
 
+def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
+    """The other encoder shapes the workload family names (SAM ViT-B / ViT-L, batch 1): images/s of the same
+    path at each density and at density 1.0, packed weights, position-only order."""
+    dev = "cuda:0"
+    shape = inputs.SHAPES[name]
+    g = 64
+    n = g * g
+    wts = [B.pack_block_weights(w) for w in device_weights(torch, seed, shape, g, dev)]
+    structs = [B.block_weights_struct(w) for w in wts]
+    flags = [i in shape.global_blocks for i in range(shape.depth)]
+    plan = B.EncoderPlan(structs, flags)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed + 7)
+    x0 = torch.randn((Bn, n, shape.D), generator=gen, device=dev).to(torch.bfloat16)
+    x = torch.empty_like(x0)
+    wtab = torch.from_numpy(B.ssam_build_window_table(g, shape.ws, 4)).to(dev)
+    wsig = torch.from_numpy(B.ssam_build_perm(shape.ws, shape.ws, 4)[0]).to(dev)
+    gtab = torch.from_numpy(B.ssam_build_perm(g, g, 4)[0]).to(dev)
+    scores = torch.empty((Bn, n), dtype=torch.float32, device=dev)
+    out = {"batch": Bn, "depth": shape.depth, "width": shape.D}
+    for r in list(densities) + [1.0]:
+        K = B.ssam_keep_count(n, r)
+        cl = B.make_cfg(Bn, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r)
+        cg = B.make_cfg(Bn, g, shape.D, shape.heads, shape.Dm, 0, 128, K, r)
+        keep = torch.empty((Bn, K), dtype=torch.int32, device=dev)
+        ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cl, cg), dtype=torch.uint8, device=dev)
+
+        def step():
+            x.copy_(x0)
+            B.ssam_encoder_forward(x, structs, flags, cl, cg, wtab, wsig, gtab, gtab, scores, keep, ws_buf, plan=plan)
+
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        out["dense" if r == 1.0 else f"density_{r}"] = {"ms_per_step": round(dt / steps * 1e3, 3),
+                                                         "images_per_s": round(Bn * steps / dt, 2)}
+    for r in densities:
+        out[f"density_{r}"]["speedup_over_dense"] = round(out["dense"]["ms_per_step"] / out[f"density_{r}"]["ms_per_step"], 3)
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -378,6 +425,11 @@ def main():
             tdt, _, _ = timed(cfg_l3, cfg_g3, keep3, dsteps, 1, False)
             out["density_0.3"] = {"ms_per_step": round(tdt / dsteps * 1e3, 3), "images_per_s": round(Bn * dsteps / tdt, 3),
                                   "keep": K3, "speedup_over_dense": round(d_ms / (tdt / dsteps * 1e3), 3)}
+
+    # ---- the smaller encoder shapes of the workload family, batch 1
+    if not args.no_dense and not args.no_parts and shape.name == "vit_h":
+        out["other_models"] = {"vit_b": model_leg(torch, B, inputs, "vit_b", 1, [0.4], 10, args.seed + 100),
+                               "vit_l": model_leg(torch, B, inputs, "vit_l", 1, [0.3, 0.4], 10, args.seed + 200)}
 
     # ---- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
