@@ -344,3 +344,50 @@ def test_encoder_stack_content_order(depth, g):
             z = oracle.encoder_block(z, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
                                      128 if glob else 32, r, keep_gpu[b])
         assert np.abs(z - y).max() > 1e-3
+
+
+def test_encoder_forward_under_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    memset), so a forward can be captured into a HIP graph.  The graph is replayed several times with
+    eager work and synchronisations in between; every replay must give the eager bits."""
+    announce("encoder under HIP graph")
+    shape = inputs.ModelShape("vit_g", 256, 3, 4, 512, (2,), 14)
+    g, B_, r = 28, 2, 0.4
+    n = g * g
+    wts = inputs.encoder_weights(80, shape, g)
+    rng = np.random.default_rng(81)
+    x = inputs.token_field(rng, B_, g, shape.D)
+    K = oracle.keep_count(n, r)
+    wds = [B.upload_block_weights(w, pack=True) for w in wts]
+    structs = [B.block_weights_struct(w) for w in wds]
+    flags = [i in shape.global_blocks for i in range(shape.depth)]
+    plan = B.EncoderPlan(structs, flags)
+    cfg_l = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r, content_order=True)
+    cfg_g = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, 0, 128, K, r, content_order=True)
+    nW = (-(-g // shape.ws)) ** 2
+    tabs = [torch.empty((B_, nW * 196), dtype=torch.int32, device=DEV), torch.empty((B_ * nW, 196), dtype=torch.int32, device=DEV),
+            torch.empty((B_, n), dtype=torch.int32, device=DEV), torch.empty((B_, n), dtype=torch.int32, device=DEV)]
+    x0 = dev_bf16(x.reshape(B_, n, shape.D))
+    xs = torch.empty_like(x0)
+    scores = torch.empty((B_, n), dtype=torch.float32, device=DEV)
+    keep = torch.empty((B_, K), dtype=torch.int32, device=DEV)
+    ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cfg_l, cfg_g), dtype=torch.uint8, device=DEV)
+
+    def step():
+        xs.copy_(x0)
+        B.ssam_encoder_forward(xs, structs, flags, cfg_l, cfg_g, tabs[0], tabs[1], tabs[2], tabs[3], scores, keep, ws_buf,
+                               plan=plan)
+
+    step()
+    torch.cuda.synchronize()
+    eager = xs.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for i in range(4):
+        xs.zero_()                                   # eager work between replays
+        ws_buf.random_(0, 255)                       # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xs, eager), f"replay {i} differs from the eager result"
