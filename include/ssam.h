@@ -150,7 +150,7 @@ int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, 
  * epilogue ldc is the row stride of the destination), and an optional device
  * workspace (NULL/0 for none; 16-byte aligned; ssam_linear_workspace_bytes()
  * is always enough, smaller is allowed).  With a workspace, a left-over launch
- * of few tiles over a long K (K >= 2048) is cut along K as well: partial fp32
+ * of few tiles (K >= 1024) is cut along K as well: partial fp32
  * tiles go to the workspace and are added in a fixed order, so results are
  * reproducible; they can differ from the no-workspace result in the last bit
  * of the fp32 sum.  The workspace is scratch: contents undefined afterwards,

@@ -65,7 +65,7 @@ static int routed_mlp_impl(void *x, const int32_t *keep_idx, const float *ln_g, 
     int rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
-    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, packed, SSAM_EPI_BIAS_GELU, none, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, packed, SSAM_EPI_BIAS_GELU, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
     if (rc != SSAM_OK) return rc;
     GemmRowMap scatter = { keep_idx, K, K, N };
     return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, GemmLd{ Dm, Dm, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0,
@@ -85,7 +85,7 @@ extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
     BlockGeom g;
     if (!block_geom(cfg, g)) return 0;
     size_t rows = (size_t)cfg->B * g.Nout;
-    size_t attn = align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2);
+    size_t attn = align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2) + GEMM_SPLIT_WS_BYTES;
     size_t mlp = mlp_ws_bytes(cfg->B, cfg->K, cfg->D, cfg->Dm);
     return attn > mlp ? attn : mlp;
 }
@@ -105,6 +105,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     unsigned char *ws = (unsigned char *)workspace;
     void *u = ws;                                             // LN1(x) in scan order; later the attention output
     void *qkv = ws + align256((size_t)rows * D * 2);
+    void *split = ws + align256((size_t)rows * D * 2) + align256((size_t)rows * 3 * D * 2);   // K-split scratch of the left-over launches
     hipStream_t st = (hipStream_t)stream;
 
     const int per_image = cfg->content_order != 0;             // tables carry a leading [B] dimension
@@ -112,7 +113,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (rc != SSAM_OK) return rc;
     GemmRowMap none = { nullptr, 1, 0, 1 };
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, w->packed != 0, SSAM_EPI_BIAS, none, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, w->packed != 0, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
     if (rc != SSAM_OK) return rc;
     if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
@@ -121,7 +122,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
                                1.0f / sqrtf((float)g.d), stream);
     if (rc != SSAM_OK) return rc;
     GemmRowMap back = { gather_table, g.Nout, per_image ? g.Nout : 0, g.N };
-    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, w->packed != 0, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, nullptr, 0, st);
+    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, w->packed != 0, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
     if (rc != SSAM_OK) return rc;
     return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, w->packed != 0,
                            B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);

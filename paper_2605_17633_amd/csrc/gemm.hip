@@ -17,7 +17,7 @@ TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes
     if (total < slots || p.rem > slots / 2) p.rem = 0;
     if (p.rem == 0) return p;
     const int n_sub = p.rem * subs;
-    int parts = nk / 8;
+    int parts = nk / 4;                         // at least 4 slabs per workgroup
     if (parts > 256 / n_sub) parts = 256 / n_sub;
     if (ws.ptr && parts >= 4 && (size_t)n_sub * parts * sub_tile_bytes <= ws.bytes) p.parts = parts;
     return p;
@@ -120,7 +120,7 @@ int pick_tile(int M, int N, int K, int epilogue, bool packed, const SplitWs &ws)
         double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
         if (plan.rem != 0) {
             const int n_sub = plan.rem * subs;
-            t += plan.parts > 1 ? ssam_div_up(nk, plan.parts) * 0.9 + 12.0 : (nk * 0.75 + 5.0) * (1.0 + n_sub / 1024.0);
+            t += plan.parts > 1 ? ssam_div_up(nk, plan.parts) * 0.9 + 11.0 : (nk * 0.75 + 5.0) * (1.0 + n_sub / 1024.0);
         }
         if (t < best_time) { best_time = t; best = c.id; }
     }

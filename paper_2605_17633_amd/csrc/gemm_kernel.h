@@ -61,7 +61,7 @@ struct GemmTileRange {
 
 constexpr int GEMM_EPI_PARTIAL = 3;   // internal: store the fp32 tile of one K range, no bias
 constexpr int GEMM_GROUP_M = 8;
-constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)16 << 20;   // workspace that lets the left-over launch cut K
+constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)32 << 20;   // workspace that lets the left-over launch cut K
 
 struct GemmSplit {
     float *partial;           // [tile_count*SUB_M*SUB_N][parts][BM][BN] fp32, NULL unless GEMM_EPI_PARTIAL
