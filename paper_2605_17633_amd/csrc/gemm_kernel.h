@@ -322,9 +322,12 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         __syncthreads();                        // every wave is done with the pipeline buffers
         if (tid < BM) dst_row[tid] = mine;
     }
+    __syncthreads();                            // pipeline buffers free for staging; dst_row visible
+    // From here on a wave touches only its own staging region: LDS operations of one wave execute in
+    // order, so the slices need no workgroup barrier (which would also wait for the previous slice's
+    // global stores); wavefront fences keep the compiler from reordering the LDS accesses.
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-        __syncthreads();
         uint4 old[PASSES];
         int drow[PASSES];
         if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
@@ -339,7 +342,8 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 stage[(8 * (r >> 2) + 4 * half + (r & 3)) * EPS + j * 32 + l32] = acc[i][j][r];
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int row = pass * RPP + rl;
@@ -370,6 +374,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // the slice is read before the next one is staged
     }
 }
 
