@@ -116,8 +116,9 @@ def profile_traffic(model):
 
 
 def encoder_flops(shape, g, B, r, rho, K):
-    """Algorithmic FLOPs of one step (per batch), on real tokens for the MLP and on padded
-    window slots for qkv/proj of local blocks (the rows the kernels really multiply)."""
+    """Algorithmic FLOPs of one step (per batch): qkv, proj and the MLP on real tokens (the
+    padding slots of the windows are not multiplied: their qkv rows are the bias), attention on
+    the active tiles of every window / of the grid."""
     import math
     D, Dm, h, d = shape.D, shape.Dm, shape.heads, shape.D // shape.heads
     n = g * g
@@ -127,7 +128,7 @@ def encoder_flops(shape, g, B, r, rho, K):
     qkv_flops = []
     for i in range(shape.depth):
         glob = i in shape.global_blocks
-        rows = n if glob else rows_local
+        rows = n
         S = n if glob else shape.ws ** 2
         Bm = 128 if glob else 32
         T = -(-S // Bm)
@@ -381,7 +382,8 @@ def main():
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": profile_traffic(shape.name),
         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": shape.depth,
         "flops_per_launch": avg_flops,
-        "shape": f"M={Bn * rows_local} (local) / {Bn * n} (global), N={3 * shape.D}, K={shape.D}",
+        "shape": f"M={Bn * n} (real tokens; the {Bn * (rows_local - n)} padding slots of the windows are filled with the bias), "
+                 f"N={3 * shape.D}, K={shape.D}",
         "qkv_share_of_step": round(float(qkv_ms.sum(axis=1).mean()) / ms_per_step, 4),
     }
 

@@ -119,7 +119,8 @@ int ssam_build_content_tables(const float *scores, int B, int g, int ws, int G,
 typedef enum ssam_epilogue {
     SSAM_EPI_BIAS = 0,        /* C = A W^T + b                                         */
     SSAM_EPI_BIAS_GELU = 1,   /* C = gelu_erf(A W^T + b)                               */
-    SSAM_EPI_BIAS_SCATTER_ADD = 2 /* C[dst(m)] += A W^T + b, dst from a row map (below) */
+    SSAM_EPI_BIAS_SCATTER_ADD = 2, /* C[dst(m)] += A W^T + b, dst from a row map (below) */
+    SSAM_EPI_BIAS_SCATTER = 3     /* C[dst(m)]  = A W^T + b, same row map                */
 } ssam_epilogue;
 
 /* C = epilogue(A W^T + bias).  A dev bf16 [M][K]; W dev bf16 [N][K]; bias dev
@@ -128,8 +129,9 @@ typedef enum ssam_epilogue {
  * added into row b*dst_rows_per_batch + row_map[b*map_batch_stride + p] of C
  * (skipped where the map is negative); C holds the residual stream and is
  * updated in place: new = bf16(old + acc + bias).  The map must not repeat a
- * row within a batch item.  Other epilogues ignore the map arguments and write
- * C [M][N]. */
+ * row within a batch item.  SSAM_EPI_BIAS_SCATTER stores bf16(acc + bias) into
+ * the mapped row instead of adding.  Other epilogues ignore the map arguments
+ * and write C [M][N]. */
 int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
                 int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
                 int dst_rows_per_batch, void *stream);
@@ -190,13 +192,15 @@ int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *strea
  *   sigma    dev int32: sigma_group_stride = 0: one table [S] shared by all groups (the
  *            position-only order); otherwise group g reads sigma + g*sigma_group_stride
  *            (>= S; the per-image, per-window tables of ssam_build_content_tables)
- *   out      dev bf16 [groups][S][h*d]
+ *   out      dev bf16, rows of h*d: query p of group g is written to row g*S+p, or, with
+ *            out_rows dev int32 [groups*S] != NULL, to row out_rows[g*S+p] (negative: not
+ *            written; used to drop the padding queries of windows and compact the rest)
  * Built for d in {64, 80} (d % 16 == 0, d <= 96 accepted), mask_block = 32 with
  * S <= 224 (windows) and mask_block = 128 with S <= 16384 (global); otherwise
  * SSAM_EUNSUPPORTED. */
 int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,
                           const void *rel_h, const void *rel_w, const int32_t *sigma,
-                          long sigma_group_stride, void *out,
+                          long sigma_group_stride, void *out, const int32_t *out_rows,
                           int groups, int S, int w, int h, int d, int mask_block, double r,
                           float scale, void *stream);
 

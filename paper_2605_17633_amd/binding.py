@@ -214,7 +214,7 @@ def ssam_linear_ld(A, W, bias, C_out=None, epilogue=EPI_BIAS, row_map=None, rows
 
 
 # ------------------------------------------------------------------ attention
-def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None, out=None):
+def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None, out=None, out_rows=None):
     """qkv: packed [groups, S, 3, h, d] bf16; sigma [S] shared, or [groups, S] per group.  Returns [groups, S, h*d]."""
     groups, S, three, h, d = qkv.shape
     assert three == 3
@@ -228,7 +228,7 @@ def ssam_sparse_attention(qkv, rel_h, rel_w, sigma, w, mask_block, r, scale=None
     _check("ssam_sparse_attention", lib().ssam_sparse_attention(
         C.c_void_p(base), C.c_void_p(base + h * d * esz), C.c_void_p(base + 2 * h * d * esz), C.c_long(3 * h * d),
         _bf(rel_h, "rel_h"), _bf(rel_w, "rel_w"), _i32(sigma, "sigma"), C.c_long(S if sigma.dim() == 2 else 0),
-        _bf(out, "out"),
+        _bf(out, "out"), _i32(out_rows, "out_rows"),
         C.c_int(groups), C.c_int(S), C.c_int(w), C.c_int(h), C.c_int(d), C.c_int(mask_block), C.c_double(r),
         C.c_float(scale), _stream()))
     return out

@@ -43,6 +43,7 @@ struct AttnParams {
     const int32_t *sigma;
     long sigma_stride;      // elements between the sigma tables of consecutive groups; 0 = one shared table
     bf16 *out;
+    const int32_t *out_rows;   // NULL: query p of group g goes to output row g*S+p; else to out_rows[g*S+p] (-1: dropped)
     int S, w, h, n_pre;
     float scale_log2e;
 };
@@ -222,9 +223,10 @@ __device__ __forceinline__ void load_q_frags(bf16x8 *qf, const bf16 *qrow)
 // Normalise the wave's 32 x D output tile and write it out.  The accumulators hold O^T (lane = query,
 // registers = 4-feature groups); the tile goes through a per-wave LDS staging area ([32][KSTR] bf16) so
 // that the global stores are 16 bytes per lane and cover whole rows.  `stage` may overlay LDS that only
-// this wave used (its bias rows).  orow0: output row of the wave's first query; nrows: valid queries.
+// this wave used (its bias rows).  out_head: the output tensor at this head's columns; my_row: the output
+// row of this lane's query (l & 31), negative = not stored (past S, or dropped by the row map).
 template <int D>
-__device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, bf16 *orow0, long out_stride, int nrows)
+__device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, bf16 *out_head, long out_stride, long my_row)
 {
     using C = AttnCfg<D>;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
@@ -245,12 +247,15 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // LDS is in order per wave; keep the compiler from reordering
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int row_lo = (int)my_row, row_hi = (int)(my_row >> 32);
 #pragma unroll
     for (int i = 0; i < (32 * C::CH + 63) / 64; ++i) {
         int id = lane + 64 * i, row = id / C::CH, c = id % C::CH;
-        if (id < 32 * C::CH && row < nrows) {
+        row = row < 32 ? row : 31;
+        const long orow = ((long)__shfl(row_hi, row, 64) << 32) | (unsigned)__shfl(row_lo, row, 64);   // lane `row` holds query `row`
+        if (id < 32 * C::CH && orow >= 0) {
             u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * C::KSTR + c * 8);
-            *reinterpret_cast<u32x4 *>(orow0 + (long)row * out_stride + c * 8) = v;
+            *reinterpret_cast<u32x4 *>(out_head + orow * out_stride + c * 8) = v;
         }
     }
 }
@@ -355,6 +360,11 @@ attn_window_kernel(AttnParams P, int n_groups)
     if (prob >= 0) WIN_PREFETCH(prob)
     for (; prob >= 0; lp += nslots, prob = local_problem(lp)) {
         const int grp = prob / P.h, head = prob % P.h;
+        long my_row = -1;                         // output row of this lane's query, looked up long before it is needed
+        if (qpos < S) {
+            my_row = (long)grp * S + qpos;
+            if (P.out_rows) my_row = P.out_rows[my_row];
+        }
         LDS_BARRIER();                            // every wave is done with the previous problem's LDS (output stores stay in flight)
 #pragma unroll
         for (int i = 0; i < WIN_MAX_LOADS; ++i) {
@@ -395,8 +405,7 @@ attn_window_kernel(AttnParams P, int n_groups)
             else
                 attn_chunk_step<D, WIN_NB, false, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
         }
-        finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + q0) * ((long)P.h * D) + (long)head * D,
-                            (long)P.h * D, min(32, S - q0));
+        finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
     }
 }
 
@@ -445,6 +454,11 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
     load_q_frags<D>(qf, P.q + base + (long)qclamp * P.row_stride);
     const int32_t *sg = P.sigma + (long)grp * P.sigma_stride;
     const uint32_t qrc = key_row_col(sg, qclamp, S, P.w);
+    long my_row = -1;                             // output row of this lane's query
+    if (qpos < S) {
+        my_row = (long)grp * S + qpos;
+        if (P.out_rows) my_row = P.out_rows[my_row];
+    }
     GlbTab *tq = reinterpret_cast<GlbTab *>(Tb + wave * wsb);
 
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
@@ -499,9 +513,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
                 attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
         }
     }
-    const int qw0 = qt * GLB_TILE + wave * 32;
-    finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + ((long)grp * S + qw0) * ((long)P.h * D) + (long)head * D,
-                        (long)P.h * D, min(32, S - qw0));
+    finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
 }
 
 template <int D>
@@ -541,7 +553,7 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
 
 extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,
                                      const void *rel_h, const void *rel_w, const int32_t *sigma,
-                                     long sigma_group_stride, void *out,
+                                     long sigma_group_stride, void *out, const int32_t *out_rows,
                                      int groups, int S, int w, int h, int d, int mask_block, double r,
                                      float scale, void *stream)
 {
@@ -567,6 +579,7 @@ extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v
     P.sigma = sigma;
     P.sigma_stride = sigma_group_stride;
     P.out = (bf16 *)out;
+    P.out_rows = out_rows;
     P.S = S; P.w = w; P.h = h;
     P.n_pre = ssam_prefix_tiles(ssam_div_up(S, mask_block), r);
     P.scale_log2e = scale * LOG2E;

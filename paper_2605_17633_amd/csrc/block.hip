@@ -9,6 +9,11 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
                      const GemmLd &ld, bool packed, int epilogue, const GemmRowMap &rm, int tile,
                      void *split_ws, size_t split_ws_bytes, hipStream_t st);
 
+int ssam_compact_slots(const int32_t *table, int table_batch_stride, int B, int Nout, int N,
+                       int32_t *real_slot, int32_t *real_spatial, int32_t *slot_row, int32_t *pad_slot, hipStream_t st);
+int ssam_fill_bias_rows(void *C, long ldc, const float *bias, int n_cols, const int32_t *pad_slot, int npad,
+                        int rows_per_batch, int B, hipStream_t st);
+
 namespace {
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -38,6 +43,31 @@ size_t mlp_core_bytes(int B, int K, int D, int Dm)
 }
 
 size_t mlp_ws_bytes(int B, int K, int D, int Dm) { return mlp_core_bytes(B, K, D, Dm) + GEMM_SPLIT_WS_BYTES; }
+
+// Tables that let the dense contractions of a windowed block skip the padding slots (see
+// compact_slots_kernel): real_slot, real_spatial [B][N], slot_row [B][Nout], pad_slot [B][Nout-N].
+struct PadTables {
+    int32_t *real_slot, *real_spatial, *slot_row, *pad_slot;
+};
+
+size_t pad_tables_bytes(int B, const BlockGeom &g)
+{
+    if (g.Nout == g.N) return 0;
+    return align256((size_t)B * g.N * 4) * 2 + align256((size_t)B * g.Nout * 4) + align256((size_t)B * (g.Nout - g.N) * 4);
+}
+
+PadTables carve_pad_tables(unsigned char *p, int B, const BlockGeom &g)
+{
+    PadTables t;
+    t.real_slot = (int32_t *)p;
+    p += align256((size_t)B * g.N * 4);
+    t.real_spatial = (int32_t *)p;
+    p += align256((size_t)B * g.N * 4);
+    t.slot_row = (int32_t *)p;
+    p += align256((size_t)B * g.Nout * 4);
+    t.pad_slot = (int32_t *)p;
+    return t;
+}
 
 }  // namespace
 
@@ -80,19 +110,26 @@ extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln
     return routed_mlp_impl(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, false, B, N, D, Dm, K, workspace, workspace_bytes, stream);
 }
 
-extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
+// everything but the padding tables, which sit behind it (so that no step of either half overwrites them
+// and a stack of blocks can build them once)
+static size_t block_core_bytes(const ssam_block_cfg *cfg, const BlockGeom &g)
 {
-    BlockGeom g;
-    if (!block_geom(cfg, g)) return 0;
     size_t rows = (size_t)cfg->B * g.Nout;
     size_t attn = align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2) + GEMM_SPLIT_WS_BYTES;
     size_t mlp = mlp_ws_bytes(cfg->B, cfg->K, cfg->D, cfg->Dm);
     return attn > mlp ? attn : mlp;
 }
 
+extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
+{
+    BlockGeom g;
+    if (!block_geom(cfg, g)) return 0;
+    return block_core_bytes(cfg, g) + pad_tables_bytes(cfg->B, g);
+}
+
 static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
                               const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
-                              void *workspace, size_t workspace_bytes, void **qkv_events, void *stream)
+                              void *workspace, size_t workspace_bytes, void **qkv_events, bool pad_tables_ready, void *stream)
 {
     BlockGeom g;
     if (!x || !w || !gather_table || !sigma || !keep_idx || !workspace || !block_geom(cfg, g)) return SSAM_EINVAL;
@@ -101,30 +138,63 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (cfg->D % 128 != 0 || cfg->Dm % 128 != 0) return SSAM_EUNSUPPORTED;
     if (workspace_bytes < ssam_encoder_block_workspace_bytes(cfg)) return SSAM_EWORKSPACE;
     const int B = cfg->B, D = cfg->D;
-    const int rows = B * g.Nout;
+    const int rows = B * g.Nout;                               // slots of the scan-order layout (with padding)
+    const bool padded = g.Nout != g.N;
+    const int crows = B * g.N;                                 // rows the dense contractions multiply (real tokens)
     unsigned char *ws = (unsigned char *)workspace;
     void *u = ws;                                             // LN1(x) in scan order; later the attention output
     void *qkv = ws + align256((size_t)rows * D * 2);
-    void *split = ws + align256((size_t)rows * D * 2) + align256((size_t)rows * 3 * D * 2);   // K-split scratch of the left-over launches
+    unsigned char *split = ws + align256((size_t)rows * D * 2) + align256((size_t)rows * 3 * D * 2);   // K-split scratch of the left-over launches
     hipStream_t st = (hipStream_t)stream;
-
     const int per_image = cfg->content_order != 0;             // tables carry a leading [B] dimension
-    int rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
-    if (rc != SSAM_OK) return rc;
-    GemmRowMap none = { nullptr, 1, 0, 1 };
-    if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-    rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, w->packed != 0, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
-    if (rc != SSAM_OK) return rc;
-    if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
     const bf16 *qp = (const bf16 *)qkv;
-    rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u,
-                               B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
-                               1.0f / sqrtf((float)g.d), stream);
-    if (rc != SSAM_OK) return rc;
-    GemmRowMap back = { gather_table, g.Nout, per_image ? g.Nout : 0, g.N };
-    rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, w->packed != 0, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
-    if (rc != SSAM_OK) return rc;
-    return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, w->packed != 0,
+    const bool packed = w->packed != 0;
+    GemmRowMap none = { nullptr, 1, 0, 1 };
+    int rc;
+
+    if (!padded) {
+        rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
+        if (rc != SSAM_OK) return rc;
+        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+        rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        if (rc != SSAM_OK) return rc;
+        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
+        rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, nullptr,
+                                   B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
+                                   1.0f / sqrtf((float)g.d), stream);
+        if (rc != SSAM_OK) return rc;
+        GemmRowMap back = { gather_table, g.Nout, per_image ? g.Nout : 0, g.N };
+        rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        if (rc != SSAM_OK) return rc;
+    } else {
+        // Windows with padding: the padding slots are zero rows after LN1, so their qkv rows are the bias and
+        // their attention outputs are dropped.  LN1 gathers the N real tokens of every image into a compact
+        // [B*N][D] matrix in scan order, the qkv contraction runs on those rows and scatters them to their
+        // slots, the padding slots are filled with the bias, attention writes only the real queries (compact
+        // again), and the proj contraction scatters them back to spatial order.
+        const PadTables pt = carve_pad_tables(ws + block_core_bytes(cfg, g), B, g);
+        if (!pad_tables_ready) {
+            rc = ssam_compact_slots(gather_table, per_image ? g.Nout : 0, B, g.Nout, g.N, pt.real_slot, pt.real_spatial, pt.slot_row, pt.pad_slot, st);
+            if (rc != SSAM_OK) return rc;
+        }
+        rc = ssam_ln_gather(x, pt.real_spatial, g.N, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.N, D, stream);
+        if (rc != SSAM_OK) return rc;
+        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+        GemmRowMap to_slot = { pt.real_slot, g.N, g.N, g.Nout };
+        rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS_SCATTER, to_slot, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        if (rc != SSAM_OK) return rc;
+        rc = ssam_fill_bias_rows(qkv, 3L * D, w->bqkv, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
+        if (rc != SSAM_OK) return rc;
+        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
+        rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, pt.slot_row,
+                                   B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
+                                   1.0f / sqrtf((float)g.d), stream);
+        if (rc != SSAM_OK) return rc;
+        GemmRowMap back = { pt.real_spatial, g.N, g.N, g.N };
+        rc = ssam_linear_impl(u, w->wproj, w->bproj, x, crows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        if (rc != SSAM_OK) return rc;
+    }
+    return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, packed,
                            B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);
 }
 
@@ -132,7 +202,7 @@ extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ss
                                   const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
                                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, stream);
+    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, false, stream);
 }
 
 extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global)
@@ -182,11 +252,23 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
     }
     rc = ssam_select_tokens(scores, keep_idx, c0->B, c0->g * c0->g, c0->K, stream);
     if (rc != SSAM_OK) return rc;
+    // the padding tables of the windowed blocks are the same for every block: built once, behind everything
+    // either kind of block writes (the global blocks' extent is smaller than the windowed ones')
+    BlockGeom gl;
+    if (any_local && block_geom(cfg_local, gl) && gl.Nout != gl.N) {
+        BlockGeom gg;
+        if (any_global && (!block_geom(cfg_global, gg) || block_core_bytes(cfg_global, gg) > block_core_bytes(cfg_local, gl)))
+            return SSAM_EINVAL;
+        const PadTables pt = carve_pad_tables((unsigned char *)workspace + block_core_bytes(cfg_local, gl), cfg_local->B, gl);
+        rc = ssam_compact_slots(window_table, cfg_local->content_order ? gl.Nout : 0, cfg_local->B, gl.Nout, gl.N,
+                                pt.real_slot, pt.real_spatial, pt.slot_row, pt.pad_slot, (hipStream_t)stream);
+        if (rc != SSAM_OK) return rc;
+    }
     for (int i = 0; i < n_blocks; ++i) {
         void **ev = qkv_events ? qkv_events + 2 * i : nullptr;
         rc = is_global[i]
-                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, ev, stream)
-                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, ev, stream);
+                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, ev, true, stream)
+                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, ev, true, stream);
         if (rc != SSAM_OK) return rc;
     }
     return SSAM_OK;

@@ -104,10 +104,10 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
 // left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
 int pick_tile(int M, int N, int K, int epilogue, bool packed, const SplitWs &ws)
 {
-    struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[3]; };
-    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5 } },
-                            { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5 } },
-                            { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8 } } };
+    struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[4]; };   // t_epi: bias, +GELU, scatter-add, scatter
+    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
+                            { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5, 4.5 } },
+                            { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8, 4.0 } } };
     const int nk = K / GEMM_BK;
     int best = 3;
     double best_time = 1e30;
@@ -142,6 +142,7 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
         case SSAM_EPI_BIAS: return launch_tile_packed<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
         case SSAM_EPI_BIAS_GELU: return launch_tile_packed<SSAM_EPI_BIAS_GELU>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
         case SSAM_EPI_BIAS_SCATTER_ADD: return launch_tile_packed<SSAM_EPI_BIAS_SCATTER_ADD>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+        case SSAM_EPI_BIAS_SCATTER: return launch_tile_packed<SSAM_EPI_BIAS_SCATTER>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
         default: return SSAM_EINVAL;
         }
     }
@@ -149,6 +150,7 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
     case SSAM_EPI_BIAS: return launch_tile<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
     case SSAM_EPI_BIAS_GELU: return launch_tile<SSAM_EPI_BIAS_GELU>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
     case SSAM_EPI_BIAS_SCATTER_ADD: return launch_tile<SSAM_EPI_BIAS_SCATTER_ADD>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
+    case SSAM_EPI_BIAS_SCATTER: return launch_tile<SSAM_EPI_BIAS_SCATTER>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
     default: return SSAM_EINVAL;
     }
 }
@@ -193,7 +195,7 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, in
     if (tile < 0 || tile > 4) return SSAM_EINVAL;
     if (w_packed && (tile == 2 || tile == 4)) return SSAM_EUNSUPPORTED;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
-    if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD) {
+    if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD || epilogue == SSAM_EPI_BIAS_SCATTER) {
         if (!row_map || rows_per_batch <= 0 || map_batch_stride < 0 || dst_rows_per_batch <= 0) return SSAM_EINVAL;
         rm = { row_map, rows_per_batch, map_batch_stride, dst_rows_per_batch };
     } else if (epilogue != SSAM_EPI_BIAS && epilogue != SSAM_EPI_BIAS_GELU) {

@@ -59,7 +59,7 @@ struct GemmTileRange {
     int tile_begin, tile_count;   // parent tiles of this launch, in band order
 };
 
-constexpr int GEMM_EPI_PARTIAL = 3;   // internal: store the fp32 tile of one K range, no bias
+constexpr int GEMM_EPI_PARTIAL = 8;   // internal: store the fp32 tile of one K range, no bias
 constexpr int GEMM_GROUP_M = 8;
 constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)32 << 20;   // workspace that lets the left-over launch cut K
 
@@ -312,7 +312,8 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     // one memory round trip instead of one per pass.
     constexpr int PASSES = 32 / RPP;
     int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + WGM * WGN * 32 * EPS);   // [BM], -1 = skip
-    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+    constexpr bool MAPPED = EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER;
+    if (MAPPED) {
         int mine = -1;
         if (tid < BM && m0 + tid < M) {
             int m = m0 + tid, b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
@@ -330,11 +331,12 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     for (int i = 0; i < MT; ++i) {
         uint4 old[PASSES];
         int drow[PASSES];
-        if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+        if (MAPPED) {
 #pragma unroll
             for (int pass = 0; pass < PASSES; ++pass) {
                 drow[pass] = dst_row[wm + i * 32 + pass * RPP + rl];
-                if (drow[pass] >= 0) old[pass] = *reinterpret_cast<const uint4 *>(C + (long)drow[pass] * ld.c + ncol);
+                if (EPI == SSAM_EPI_BIAS_SCATTER_ADD && drow[pass] >= 0)
+                    old[pass] = *reinterpret_cast<const uint4 *>(C + (long)drow[pass] * ld.c + ncol);
             }
         }
 #pragma unroll
@@ -370,6 +372,8 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] += o[e];
                 *reinterpret_cast<uint4 *>(C + (long)drow[pass] * ld.c + ncol) = pack_bf16x8(v);
+            } else if (EPI == SSAM_EPI_BIAS_SCATTER) {
+                if (drow[pass] >= 0) *reinterpret_cast<uint4 *>(C + (long)drow[pass] * ld.c + ncol) = pack_bf16x8(v);
             } else {
                 *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);
             }
@@ -415,15 +419,17 @@ gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const floa
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
     }
-    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER) {
         int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
         int idx = rm.map[(long)b * rm.map_batch_stride + p];
         if (idx < 0 || idx >= rm.dst_rows_per_batch) return;
         uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)b * rm.dst_rows_per_batch + idx) * ld.c + ncol);
-        float o[8];
-        unpack_bf16x8(*dst, o);
+        if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
+            float o[8];
+            unpack_bf16x8(*dst, o);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += o[e];
+            for (int e = 0; e < 8; ++e) v[e] += o[e];
+        }
         *dst = pack_bf16x8(v);
     } else {
         *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);

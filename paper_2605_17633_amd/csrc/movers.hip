@@ -258,6 +258,64 @@ static int mover_grid(long total_chunks)
     return (int)(blocks < 1 ? 1 : (blocks > 256L * 32 ? 256L * 32 : blocks));
 }
 
+// ---------------------------------------------------------------- padding compaction
+// SAM pads the grid up to a multiple of the window; padding slots are zero rows after LN1, so their
+// qkv rows equal the bias and their attention outputs are dropped.  One workgroup per image walks the
+// gather table (slot -> spatial index, -1 = padding) in slot order and writes
+//   real_slot[b][c]    the slot of the c-th real token (c-th row of the compact activations)
+//   real_spatial[b][c] its spatial index
+//   slot_row[b][s]     b*N + c for a real slot (the compact row), -1 for padding
+//   pad_slot[b][i]     the i-th padding slot
+// so that the dense contractions run on the N real rows only.
+__global__ void __launch_bounds__(SEL_THREADS)
+compact_slots_kernel(const int32_t *__restrict__ table, int table_batch_stride, int Nout, int N,
+                     int32_t *__restrict__ real_slot, int32_t *__restrict__ real_spatial,
+                     int32_t *__restrict__ slot_row, int32_t *__restrict__ pad_slot)
+{
+    __shared__ int scratch[SEL_THREADS / 64];
+    const int b = blockIdx.x, npad = Nout - N;
+    const int32_t *t = table + (long)b * table_batch_stride;
+    int base = 0;
+    for (int s0 = 0; s0 < Nout; s0 += SEL_THREADS) {
+        const int s = s0 + threadIdx.x;
+        const int v = s < Nout ? t[s] : -1;
+        const bool real = s < Nout && v >= 0 && v < N;
+        int total;
+        const int c = base + block_exclusive_count(real, scratch, total);
+        if (s < Nout) {
+            if (real) {
+                if (c < N) {
+                    real_slot[(long)b * N + c] = s;
+                    real_spatial[(long)b * N + c] = v;
+                }
+                slot_row[(long)b * Nout + s] = c < N ? b * N + c : -1;
+            } else {
+                const int pc = s - c;
+                if (pc < npad) pad_slot[(long)b * npad + pc] = s;
+                slot_row[(long)b * Nout + s] = -1;
+            }
+        }
+        base += total;
+    }
+}
+
+// rows[b*rows_per_batch + pad_slot[b][i]] = bf16(bias): one wave per row, 16 bytes per lane
+__global__ void __launch_bounds__(256)
+fill_bias_rows_kernel(bf16 *__restrict__ C, long ldc, const float *__restrict__ bias, int n_cols,
+                      const int32_t *__restrict__ pad_slot, int npad, int rows_per_batch, int total_rows)
+{
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= total_rows) return;
+    const int b = r / npad, i = r - b * npad;
+    bf16 *dst = C + ((long)b * rows_per_batch + pad_slot[(long)b * npad + i]) * ldc;
+    for (int c = lane * 8; c < n_cols; c += 64 * 8) {
+        const float4 *b4 = reinterpret_cast<const float4 *>(bias + c);
+        float4 x0 = b4[0], x1 = b4[1];
+        float v[8] = { x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w };
+        *reinterpret_cast<uint4 *>(dst + c) = pack_bf16x8(v);
+    }
+}
+
 // ---------------------------------------------------------------- content-aware order
 // One workgroup per (image, window): the window's cells are ranked by (score descending, cell index
 // ascending; padding cells last) with a bitonic sort of 64-bit keys in LDS, then the stripe interleave
@@ -400,6 +458,27 @@ extern "C" int ssam_build_content_tables(const float *scores, int B, int g, int 
         return SSAM_EHIP;
     hipLaunchKernelGGL(content_tables_kernel, dim3(B * nws * nws), dim3(threads), lds, (hipStream_t)stream,
                        scores, g, w, nws, G, P, gather_table, sigma);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+// internal (block composition): see compact_slots_kernel / fill_bias_rows_kernel
+int ssam_compact_slots(const int32_t *table, int table_batch_stride, int B, int Nout, int N,
+                       int32_t *real_slot, int32_t *real_spatial, int32_t *slot_row, int32_t *pad_slot, hipStream_t st)
+{
+    hipLaunchKernelGGL(compact_slots_kernel, dim3(B), dim3(SEL_THREADS), 0, st, table, table_batch_stride, Nout, N,
+                       real_slot, real_spatial, slot_row, pad_slot);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+int ssam_fill_bias_rows(void *C, long ldc, const float *bias, int n_cols, const int32_t *pad_slot, int npad,
+                        int rows_per_batch, int B, hipStream_t st)
+{
+    const int total = B * npad;
+    if (total <= 0) return SSAM_OK;
+    hipLaunchKernelGGL(fill_bias_rows_kernel, dim3(ssam_div_up(total, 4)), dim3(256), 0, st, (bf16 *)C, ldc, bias, n_cols,
+                       pad_slot, npad, rows_per_batch, total);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }
