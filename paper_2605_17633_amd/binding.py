@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssam.so")
 _lib = None
 
-EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_SCATTER_ADD = 0, 1, 2
+EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_SCATTER_ADD, EPI_BIAS_SCATTER = 0, 1, 2, 3
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 

@@ -230,6 +230,11 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
 {
     using C = AttnCfg<D>;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    // the last P V MFMAs may still be in flight and this point is reached through loop-exit branches:
+    // wait their passes out explicitly before the accumulators are read (see the GEMM epilogue)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     const float l = st.l + __shfl_xor(st.l, 32, 64);
     const float inv = 1.0f / l;
 #pragma unroll

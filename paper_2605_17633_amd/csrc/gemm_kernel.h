@@ -289,6 +289,14 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     }
     }
 
+    // The last MFMAs are still in flight here.  Reads of their accumulator registers need up to 18 wait
+    // states after a 16-pass MFMA, which the compiler inserts within straight-line code; the epilogue starts
+    // with wave-divergent branches (row-map look-ups by some waves only), and one instantiation read its last
+    // accumulator register too early on the waves that skip the branch.  Wait the passes out explicitly.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- epilogue: 32-row slices through a per-wave fp32 LDS region
     constexpr int EPS = WN + 4;                 // floats per staged row (16-byte multiple, odd in 16-byte units)
     constexpr int LPR = WN / 8;                 // lanes per row when each lane owns 8 columns

@@ -74,6 +74,28 @@ def test_attention_stress_peaky_softmax(w, d, Bm, r):
     assert_close(got, ref, f"stress attention w={w} d={d}")
 
 
+@pytest.mark.parametrize("w,Bm", [(14, 32), (32, 128)])
+def test_attention_output_row_map(w, Bm):
+    """out_rows: queries are written to the rows the map names and dropped where it is negative; the
+    values are those of the unmapped call, bit for bit."""
+    announce("attention out_rows", w, Bm)
+    rng = np.random.default_rng(33)
+    groups, h, d, S = 3, 2, 80, w * w
+    qkv = dev_bf16(inputs.bf16_round(rng.normal(size=(groups, S, 3, h, d)).astype(np.float32) * 0.7))
+    rel_h, rel_w = (dev_bf16(inputs.bf16_round(rng.normal(size=(2 * w - 1, d)).astype(np.float32) * 0.1)) for _ in range(2))
+    sig = dev_i32(oracle.grid_sigma(w, 4)[0])
+    plain = B.ssam_sparse_attention(qkv, rel_h, rel_w, sig, w, Bm, 0.4)
+    keep = rng.random(groups * S) < 0.8
+    rows = np.full(groups * S, -1, np.int32)
+    rows[keep] = rng.permutation(int(keep.sum())).astype(np.int32)
+    out = torch.full((int(keep.sum()) + 5, h * d), 9.0, dtype=torch.bfloat16, device=DEV)
+    B.ssam_sparse_attention(qkv, rel_h, rel_w, sig, w, Bm, 0.4, out=out, out_rows=dev_i32(rows))
+    torch.cuda.synchronize()
+    flat = plain.reshape(groups * S, h * d)
+    assert torch.equal(out[torch.from_numpy(rows[keep]).long().to(DEV)], flat[torch.from_numpy(np.nonzero(keep)[0]).to(DEV)])
+    assert bool((out[int(keep.sum()):] == 9.0).all())
+
+
 def test_attention_plain_morton_order():
     announce("attention G=1")
     got, ref = run_attention_case(2, 14, 2, 64, 32, 0.4, G=1)

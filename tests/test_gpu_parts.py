@@ -234,6 +234,33 @@ def test_linear_packed_weights(tile, M, N, K, epi):
     assert e.value.code == B.EUNSUPPORTED
 
 
+@pytest.mark.parametrize("tile,M,N,K,packed", [(0, 500, 256, 128, False), (1, 8400, 2048, 2048, True), (3, 4200, 2048, 128, False)])
+def test_linear_mapped_store(tile, M, N, K, packed):
+    """SSAM_EPI_BIAS_SCATTER: row m of the product is stored at the mapped row (negative: dropped), the rows
+    the map does not name keep their bits; plain, left-over and K-split launches."""
+    announce("linear mapped store", tile, M, N, K, packed)
+    rng = np.random.default_rng(19)
+    A = inputs.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = inputs.bf16_round((rng.normal(size=(N, K)) / np.sqrt(K)).astype(np.float32))
+    b = rng.normal(size=N).astype(np.float32)
+    rows_out = M + 77
+    dst = rng.permutation(rows_out)[:M].astype(np.int32)
+    dst[3] = -1
+    Wd = dev_bf16(W)
+    if packed:
+        Wd = B.ssam_pack_weight(Wd)
+    ws = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    out = torch.full((rows_out, N), 5.0, dtype=torch.bfloat16, device=DEV)
+    B.ssam_linear_ld(dev_bf16(A), Wd, dev_f32(b), out, epilogue=B.EPI_BIAS_SCATTER, row_map=dev_i32(dst), rows_per_batch=M,
+                     map_batch_stride=0, dst_rows_per_batch=rows_out, tile=tile, workspace=ws, w_packed=packed)
+    got = to_np(out)
+    ref = _gemm_ref(A, W, b)
+    ok = dst >= 0
+    assert_close(got[dst[ok]], ref[ok], "mapped store", tol=1e-2)
+    untouched = np.setdiff1d(np.arange(rows_out), dst[ok])
+    assert np.all(got[untouched] == 5.0)
+
+
 def test_linear_row_strides():
     """Operands and result as column slices of wider buffers: strides are honoured, padding untouched."""
     announce("linear strides")
