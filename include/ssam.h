@@ -138,7 +138,7 @@ int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M,
 
 /* The same with the workgroup tile forced (tuning and tests): tile = 0 picks
  * automatically, 1 = 256x256 with 8 waves (needs N % 256 == 0), 2 = 256x128,
- * 3 = 128x128, 4 = 256x256 with 4 waves.
+ * 3 = 128x128.
  * With any tile, when the tiles fill at least one round of workgroups and the
  * left-over is under half a round, the left-over tiles run as a second launch
  * of half- or quarter-size tiles; results do not depend on the tile choice

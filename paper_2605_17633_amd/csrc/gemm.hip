@@ -92,7 +92,6 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
     case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
-    case 4: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     default: return SSAM_EINVAL;
     }
 }
@@ -192,8 +191,8 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, in
     if (lda < K || ldc < N || lda % 8 || ldc % 8 || (!w_packed && (ldw < K || ldw % 8))) return SSAM_EINVAL;
     if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
     if (N % 128 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
-    if (tile < 0 || tile > 4) return SSAM_EINVAL;
-    if (w_packed && (tile == 2 || tile == 4)) return SSAM_EUNSUPPORTED;
+    if (tile < 0 || tile > 3) return SSAM_EINVAL;
+    if (w_packed && tile == 2) return SSAM_EUNSUPPORTED;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
     if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD || epilogue == SSAM_EPI_BIAS_SCATTER) {
         if (!row_map || rows_per_batch <= 0 || map_batch_stride < 0 || dst_rows_per_batch <= 0) return SSAM_EINVAL;
