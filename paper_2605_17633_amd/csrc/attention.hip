@@ -102,6 +102,9 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
                 if (ok) a = *reinterpret_cast<const bf16x8 *>(rel + (long)mrow * rstr + ks * 16 + half * 8);
                 u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], u, 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");          // MFMA passes done before u is read under predicates
+            __builtin_amdgcn_sched_barrier(0);
             TabT *dst = tq + l32 * 2 * ts + (tab ? ts : 0);
             const int qpos = tab ? qcol : qrow;
 #pragma unroll
@@ -141,6 +144,11 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
             }
         }
     }
+    // the score MFMAs sit behind wave-uniform branches (b < nb): wait their passes out before the reads
+    // (the compiler's hazard handling is only relied upon within straight-line code; see the GEMM epilogue)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     float mx = st.m;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
