@@ -16,6 +16,7 @@ Extra legs (run after the timed region, reported inside the same JSON line):
   dense, density_0.3, content_order   the same kernels at density 1.0 (the "dense GPU block"), at 0.3,
                 and at 0.4 with the content-aware order of Sec. 4.1 (per-image tables)
   other_models  SAM ViT-B and ViT-L shaped encoders at batch 1 (sparse and dense)
+  kernels_batch16  isolated global attention and routed MLP at batch 16 over densities 0.2 .. 1.0
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -223,6 +224,61 @@ def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab,
     ms = run(lambda: B.ssam_select_tokens(scores, K, keep_idx=keep))
     parts["select_tokens"] = {"us": round(ms * 1e3, 1), "bound": "latency", "once_per": "image, shared by all blocks"}
     return parts
+
+
+def sweep_leg(torch, hip, B, inputs, seed, reps=5):
+    """The isolated ViT-H-dim kernels at batch 16 swept over densities (global Stripe-Sort attention over
+    4096 tokens x 16 heads x 80; routed MLP 1280 -> 5120 -> 1280 with lognormal scores), each against the
+    bf16 MFMA peak on its algorithmic FLOPs."""
+    import math
+    dev = "cuda:0"
+    Bn, g, h, d, D, Dm = 16, 64, 16, 80, 1280, 5120
+    n = g * g
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    bf = torch.bfloat16
+    qkv = (torch.randn((Bn, n, 3, h, d), generator=gen, device=dev) * 0.7).to(bf)
+    rel_h = (torch.randn((2 * g - 1, d), generator=gen, device=dev) * 0.02).to(bf)
+    rel_w = (torch.randn((2 * g - 1, d), generator=gen, device=dev) * 0.02).to(bf)
+    sig = torch.from_numpy(B.ssam_build_perm(g, g, 4)[0]).to(dev)
+    o = torch.empty((Bn, n, D), dtype=bf, device=dev)
+    x = (torch.randn((Bn, n, D), generator=gen, device=dev)).to(bf)
+    scores = torch.exp(torch.randn((Bn, n), generator=gen, device=dev))
+    w = {"ln2_g": 1.0 + torch.randn(D, generator=gen, device=dev) * 0.02, "ln2_b": torch.randn(D, generator=gen, device=dev) * 0.02,
+         "w1": (torch.randn((Dm, D), generator=gen, device=dev) * 0.02).to(bf), "b1": torch.randn(Dm, generator=gen, device=dev) * 0.02,
+         "w2": (torch.randn((D, Dm), generator=gen, device=dev) * 0.02).to(bf), "b2": torch.randn(D, generator=gen, device=dev) * 0.02}
+    ws_buf = torch.empty(B.ssam_routed_mlp_workspace_bytes(Bn, n, D, Dm), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = hip.event(), hip.event()
+
+    def run(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        hip.record(e0, stream)
+        for _ in range(reps):
+            fn()
+        hip.record(e1, stream)
+        torch.cuda.synchronize()
+        return hip.elapsed_ms(e0, e1) / reps
+
+    out = {"batch": Bn}
+    for r in (0.2, 0.3, 0.4, 0.6, 1.0):
+        T = n // 128
+        n_pre = min(T, int(math.floor(r * T + 1e-6)))
+        tiles = n_pre * T + (T - n_pre)
+        ms_a = run(lambda: B.ssam_sparse_attention(qkv, rel_h, rel_w, sig, g, 128, r, out=o))
+        fl_a = 4.0 * 128 * 128 * d * tiles * h * Bn
+        K = B.ssam_keep_count(n, r)
+        keep = B.ssam_select_tokens(scores, K)
+        ms_m = run(lambda: B.ssam_routed_mlp(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w["w1"], w["b1"], w["w2"], w["b2"], workspace=ws_buf))
+        fl_m = 4.0 * Bn * K * D * Dm
+        out[f"density_{r}"] = {
+            "attention_global": {"us": round(ms_a * 1e3, 1), "tflops": round(fl_a / ms_a / 1e9, 1),
+                                 "frac": round(fl_a / ms_a / 1e9 / PEAK_BF16_TFLOPS, 4), "active_tiles": tiles},
+            "routed_mlp": {"us": round(ms_m * 1e3, 1), "tflops": round(fl_m / ms_m / 1e9, 1),
+                           "frac": round(fl_m / ms_m / 1e9 / PEAK_BF16_TFLOPS, 4), "keep": K}}
+    return out
 
 
 def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
@@ -446,6 +502,7 @@ def main():
     if not args.no_dense and not args.no_parts and shape.name == "vit_h":
         out["other_models"] = {"vit_b": model_leg(torch, B, inputs, "vit_b", 1, [0.4], 10, args.seed + 100),
                                "vit_l": model_leg(torch, B, inputs, "vit_l", 1, [0.3, 0.4], 10, args.seed + 200)}
+        out["kernels_batch16"] = sweep_leg(torch, hip, B, inputs, args.seed + 300)
 
     # ---- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
