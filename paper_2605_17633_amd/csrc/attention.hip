@@ -74,9 +74,10 @@ __device__ __forceinline__ void init_state(WaveState<D> &st)
     st.l = 0.f;
 }
 
-// Bias rows for the wave's 32 queries, one table row of 2*ts floats per query:
-//   tq[q*2*ts + p]      = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
-//   tq[q*2*ts + ts + p] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
+// Bias tables of the wave's 32 queries, 2*ts entries per query, stored entry-major so that the 32 lanes
+// that look up the same key (a key's row and column are the same for every query) hit consecutive banks:
+//   tq[p*32 + q]        = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
+//   tq[(ts + p)*32 + q] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
 // rel tables: rows of `rstr` elements, from global memory (rstr = D) or from a zero-padded LDS copy.
 template <int D, typename TabT>
 __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr,
@@ -105,13 +106,13 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");          // MFMA passes done before u is read under predicates
             __builtin_amdgcn_sched_barrier(0);
-            TabT *dst = tq + l32 * 2 * ts + (tab ? ts : 0);
+            TabT *dst = tq + (tab ? ts * 32 : 0) + l32;
             const int qpos = tab ? qcol : qrow;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int m = mt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 int p = qpos + (w - 1) - m;
-                if (p >= 0 && p < w && m < nrel) dst[p] = (TabT)(u[r] * LOG2E);
+                if (p >= 0 && p < w && m < nrel) dst[p * 32] = (TabT)(u[r] * LOG2E);
             }
         }
     }
@@ -119,10 +120,10 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
 
 // A chunk of nb (1..NB, wave-uniform) 32-key blocks against the wave's 32 queries.
 //   Ks, Vs: LDS, row-major rows ([keys][KSTR]); blk[b]: index of the chunk's b-th block in them
-//   krc:    LDS, per key the byte offsets of its bias entries in a query's table row:
-//           low half = 4*row, high half = 4*(ts + col); indexed like Ks
+//   krc:    LDS, per key the byte offsets of its two entries in the wave's entry-major bias tables:
+//           low half = 32*esz*row, high half = 32*esz*(ts + col); indexed like Ks
 //   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
-//   tq:     this lane's query row of the bias table
+//   tq:     the wave's bias tables at this lane's query (entry p at tq[32*p])
 template <int D, int NB, bool RAGGED, typename TabT>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
@@ -134,13 +135,12 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (b < nb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
             const bf16 *kblk = Ks + blk[b] * 32 * C::KSTR + l32 * C::KSTR + half * 8;
+            const f32x16 zero = { 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f };
 #pragma unroll
             for (int ks = 0; ks < C::KS; ++ks) {
                 bf16x8 a = *reinterpret_cast<const bf16x8 *>(kblk + ks * 16);
-                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[b], 0, 0, 0);
+                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], ks == 0 ? zero : s[b], 0, 0, 0);
             }
         }
     }
@@ -280,11 +280,11 @@ __device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int
     return (uint32_t)(cell / w) | ((uint32_t)(cell % w) << 16);
 }
 
-// the same as byte offsets into a query's bias table row (th part, then tw part at +ts floats)
+// the same as byte offsets of the key's two entries in the wave's entry-major bias tables (row part, then column part)
 __device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p, int S, int w, int ts, uint32_t esz = 4u)
 {
     uint32_t rc = key_row_col(sigma, p, S, w);
-    return (esz * (rc & 0xffffu)) | ((esz * ((uint32_t)ts + (rc >> 16))) << 16);
+    return (32u * esz * (rc & 0xffffu)) | ((32u * esz * ((uint32_t)ts + (rc >> 16))) << 16);
 }
 
 // per-wave LDS scratch: the bias rows of its 32 queries, later overlaid by its output staging tile
@@ -414,9 +414,9 @@ attn_window_kernel(AttnParams P, int n_groups)
 #pragma unroll
             for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
             if (ragged)
-                attn_chunk_step<D, WIN_NB, true, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, WIN_NB, true, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32);
             else
-                attn_chunk_step<D, WIN_NB, false, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, WIN_NB, false, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32);
         }
         finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
     }
@@ -521,9 +521,9 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             for (int b = 0; b < GLB_NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
             const int nb = min(GLB_NB, nblk - c0);
             if (key0[GLB_NB - 1] + 32 > S)
-                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32);
             else
-                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32 * 2 * ts);
+                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32);
         }
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
