@@ -240,3 +240,29 @@ def encoder(x, blocks, h: int, ws: int, global_blocks, G: int, r: float, rho: fl
         x = encoder_block(x, wt, h, 0 if is_global else ws, G, Bm_global if is_global else Bm_window,
                           r, keep, eps, order_scores=scores if content_order else None)
     return x, keep
+
+
+def patch_embed(img, w, b, pos, P: int) -> np.ndarray:
+    """img [3,H,W], w [D,3,P,P], b [D], pos [gh*gw,D] -> tokens [gh,gw,D] (SAM's patch embedding plus the
+    absolute position embedding)."""
+    img, w, b, pos = map(_f32, (img, w, b, pos))
+    _, H, W = img.shape
+    D = w.shape[0]
+    assert w.shape == (D, 3, P, P) and pos.shape == ((H // P) * (W // P), D)
+    x = np.empty(((H // P) * (W // P), D), np.float32)
+    _check(lib().oracle_patch_embed(_p(img), C.c_int(H), C.c_int(W), C.c_int(P), _p(w), _p(b), _p(pos), C.c_int(D), _p(x)),
+           "oracle_patch_embed")
+    return x.reshape(H // P, W // P, D)
+
+
+def neck(x, w1, ln1_g, ln1_b, w2, ln2_g, ln2_b, eps: float = 1e-6) -> np.ndarray:
+    """x [g,g,D]; w1 [C,D]; w2 [C,C,3,3] -> [g,g,C] (SAM's neck: 1x1 conv, LayerNorm over channels, 3x3 conv
+    with zero padding, LayerNorm over channels; no conv biases)."""
+    x, w1, ln1_g, ln1_b, w2, ln2_g, ln2_b = map(_f32, (x, w1, ln1_g, ln1_b, w2, ln2_g, ln2_b))
+    g, _, D = x.shape
+    Cn = w1.shape[0]
+    assert w1.shape == (Cn, D) and w2.shape == (Cn, Cn, 3, 3)
+    out = np.empty((g * g, Cn), np.float32)
+    _check(lib().oracle_neck(_p(x), C.c_int(g), C.c_int(D), C.c_int(Cn), _p(w1), _p(ln1_g), _p(ln1_b), _p(w2), _p(ln2_g),
+                             _p(ln2_b), C.c_double(eps), _p(out)), "oracle_neck")
+    return out.reshape(g, g, Cn)

@@ -28,7 +28,8 @@
  * content-aware order against a hand-derived example, a library sort with the
  * paper's transpose, its rank structure, and two properties of the block that
  * uses it (order irrelevant at r = 1; scores decreasing along the Z-order
- * reproduce the position-only block).
+ * reproduce the position-only block); the encoder ends (patch embedding,
+ * neck) against library convolution and layer norm and closed-form cases.
  * The paper prints no worked numeric example of the block: whole-block values
  * at r < 1 are "parity unpinned" by the paper itself and rest on the pins of
  * the parts.
@@ -523,4 +524,81 @@ int oracle_encoder_block(float *x, int g, int D, int h, int Dm, int ws, int G, i
     free(u); free(qh); free(oh); free(qkv);
     if (rc) return rc;
     return oracle_routed_mlp(x, n, D, Dm, keep, K, ln2_g, ln2_b, eps, w1, b1, w2, b2);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Encoder ends of the SAM ViT image encoder.  The paper's method lives in   */
+/* the blocks and it measures the whole encoder; it does not describe the    */
+/* ends, which follow the public SAM architecture: a patch embedding (one    */
+/* P x P, stride-P convolution = one linear map per patch) plus an absolute  */
+/* position embedding in front, and a "neck" behind (1x1 convolution without */
+/* bias, LayerNorm over channels, 3x3 convolution without bias and with zero */
+/* padding, LayerNorm over channels).  Plain definitions, double inside.     */
+/*   img [3][H][W]; w [D][3][P][P] (out, in, ky, kx); pos [gh*gw][D];        */
+/*   x [gh*gw][D], gh = H/P, gw = W/P.                                       */
+/* ------------------------------------------------------------------------ */
+int oracle_patch_embed(const float *img, int H, int W, int P, const float *w, const float *b,
+                       const float *pos, int D, float *x)
+{
+    if (!img || !w || !b || !pos || !x || H <= 0 || W <= 0 || P <= 0 || D <= 0 || H % P || W % P) return ORACLE_EINVAL;
+    const int gh = H / P, gw = W / P;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int ty = 0; ty < gh; ++ty)
+        for (int tx = 0; tx < gw; ++tx) {
+            const size_t t = (size_t)ty * gw + tx;
+            for (int o = 0; o < D; ++o) {
+                double acc = (double)b[o] + (double)pos[t * D + o];
+                for (int c = 0; c < 3; ++c)
+                    for (int ky = 0; ky < P; ++ky)
+                        for (int kx = 0; kx < P; ++kx)
+                            acc += (double)w[(((size_t)o * 3 + c) * P + ky) * P + kx] *
+                                   (double)img[((size_t)c * H + ty * P + ky) * W + tx * P + kx];
+                x[t * D + o] = (float)acc;
+            }
+        }
+    return 0;
+}
+
+/*   x [g*g][D] token-major; w1 [C][D]; w2 [C][C][3][3] (out, in, ky, kx);   */
+/*   out [g*g][C] token-major (the channel-first tensor of SAM, transposed). */
+int oracle_neck(const float *x, int g, int D, int C, const float *w1, const float *ln1_g, const float *ln1_b,
+                const float *w2, const float *ln2_g, const float *ln2_b, double eps, float *out)
+{
+    if (!x || !w1 || !ln1_g || !ln1_b || !w2 || !ln2_g || !ln2_b || !out || g <= 0 || D <= 0 || C <= 0) return ORACLE_EINVAL;
+    const int n = g * g;
+    double *y = (double *)malloc((size_t)n * C * sizeof(double));
+    if (!y) return ORACLE_ENOMEM;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < n; ++t) {
+        double *row = (double *)malloc((size_t)C * sizeof(double));
+        for (int o = 0; o < C; ++o) {
+            double acc = 0.0;
+            for (int c = 0; c < D; ++c) acc += (double)x[(size_t)t * D + c] * (double)w1[(size_t)o * D + c];
+            row[o] = acc;
+        }
+        layer_norm_row(row, ln1_g, ln1_b, eps, C, y + (size_t)t * C);
+        free(row);
+    }
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < n; ++t) {
+        const int ty = t / g, tx = t % g;
+        double *row = (double *)malloc((size_t)2 * C * sizeof(double));
+        for (int o = 0; o < C; ++o) {
+            double acc = 0.0;
+            for (int ky = 0; ky < 3; ++ky)
+                for (int kx = 0; kx < 3; ++kx) {
+                    const int sy = ty + ky - 1, sx = tx + kx - 1;
+                    if (sy < 0 || sy >= g || sx < 0 || sx >= g) continue;      /* zero padding */
+                    const double *src = y + ((size_t)sy * g + sx) * C;
+                    for (int c = 0; c < C; ++c)
+                        acc += src[c] * (double)w2[(((size_t)o * C + c) * 3 + ky) * 3 + kx];
+                }
+            row[o] = acc;
+        }
+        layer_norm_row(row, ln2_g, ln2_b, eps, C, row + C);
+        for (int o = 0; o < C; ++o) out[(size_t)t * C + o] = (float)row[C + o];
+        free(row);
+    }
+    free(y);
+    return 0;
 }
