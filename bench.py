@@ -15,6 +15,7 @@ Extra legs (run after the timed region, reported inside the same JSON line):
                 each against the roofline that bounds it
   dense, density_0.3, content_order   the same kernels at density 1.0 (the "dense GPU block"), at 0.3,
                 and at 0.4 with the content-aware order of Sec. 4.1 (per-image tables)
+  pixels_to_embedding  the whole image encoder: patch embedding, the blocks, the neck
   other_models  SAM ViT-B and ViT-L shaped encoders at batch 1 (sparse and dense)
   kernels_batch16  isolated global attention and routed MLP at batch 16 over densities 0.2 .. 1.0
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
@@ -497,6 +498,41 @@ def main():
             tdt, _, _ = timed(cfg_l3, cfg_g3, keep3, dsteps, 1, False)
             out["density_0.3"] = {"ms_per_step": round(tdt / dsteps * 1e3, 3), "images_per_s": round(Bn * dsteps / tdt, 3),
                                   "keep": K3, "speedup_over_dense": round(d_ms / (tdt / dsteps * 1e3), 3)}
+
+    # ---- pixels in -> embedding out: patch embedding + position embedding, the blocks, the neck
+    if not args.no_dense:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(args.seed + 400)
+        bf = torch.bfloat16
+        P_, C_ = 16, 256
+        img = torch.randn((Bn, 3, g * P_, g * P_), generator=gen, device=dev).to(bf)
+        w_pe = (torch.randn((shape.D, 3 * P_ * P_), generator=gen, device=dev) * 0.02).to(bf)
+        b_pe = torch.randn(shape.D, generator=gen, device=dev) * 0.02
+        pos = (torch.randn((n, shape.D), generator=gen, device=dev) * 0.02).to(bf)
+        w_n1 = (torch.randn((C_, shape.D), generator=gen, device=dev) * 0.02).to(bf)
+        w_n2 = (torch.randn((C_, 9 * C_), generator=gen, device=dev) * 0.02).to(bf)
+        ln_g, ln_b = 1.0 + torch.randn(C_, generator=gen, device=dev) * 0.02, torch.randn(C_, generator=gen, device=dev) * 0.02
+        emb = torch.empty((Bn, n, C_), dtype=bf, device=dev)
+        ws_pe = torch.empty(B.ssam_patch_embed_workspace_bytes(Bn, g * P_, g * P_, P_), dtype=torch.uint8, device=dev)
+        ws_nk = torch.empty(B.ssam_neck_workspace_bytes(Bn, g, shape.D, C_), dtype=torch.uint8, device=dev)
+
+        def step_full():
+            B.ssam_patch_embed(img, w_pe, b_pe, pos, P_, x=x, workspace=ws_pe)
+            B.ssam_encoder_forward(x, structs, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf, plan=plan)
+            B.ssam_neck(x, w_n1, ln_g, ln_b, w_n2, ln_g, ln_b, g, out=emb, workspace=ws_nk)
+
+        for _ in range(2):
+            step_full()
+        torch.cuda.synchronize()
+        fsteps = max(2, args.steps // 2)
+        t0 = time.perf_counter()
+        for _ in range(fsteps):
+            step_full()
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        out["pixels_to_embedding"] = {"ms_per_step": round(fdt / fsteps * 1e3, 3), "images_per_s": round(Bn * fsteps / fdt, 3),
+                                      "note": "1024x1024 bf16 images: patch embedding + position embedding, the 32 blocks at "
+                                              f"density {r}, neck to {C_} channels"}
 
     # ---- the smaller encoder shapes of the workload family, batch 1
     if not args.no_dense and not args.no_parts and shape.name == "vit_h":

@@ -302,6 +302,32 @@ int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8
                          float *scores, int32_t *keep_idx,
                          void *workspace, size_t workspace_bytes, void **qkv_events, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Encoder ends (public SAM architecture around the blocks)                  */
+/* ------------------------------------------------------------------------- */
+
+/* Patch embedding + absolute position embedding: tokens[b][ty*gw+tx][:] =
+ * pos[ty*gw+tx][:] + bias + sum_{c,ky,kx} w[:][c][ky][kx] img[b][c][ty*P+ky][tx*P+kx]
+ * (one rounding to bf16).  img dev bf16 [B][3][H][W]; w dev bf16 [D][3*P*P]
+ * (out, then in-channel, ky, kx: a convolution weight flattened); bias dev fp32
+ * [D]; pos dev bf16 [(H/P)*(W/P)][D]; x dev bf16 [B][(H/P)*(W/P)][D], written.
+ * P % 8 == 0, 3*P*P % 64 == 0, D % 128 == 0 (else SSAM_EUNSUPPORTED). */
+size_t ssam_patch_embed_workspace_bytes(int B, int H, int W, int P);
+int ssam_patch_embed(const void *img, const void *w, const float *bias, const void *pos, void *x,
+                     int B, int H, int W, int P, int D, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Neck: out = LN2(conv3x3(LN1(x W1^T))) per image, LayerNorm over the C
+ * channels of every token, no convolution biases, zero padding.  x dev bf16
+ * [B][g*g][D]; w1 dev bf16 [C][D]; w2 dev bf16 [C][9*C] with the input index
+ * ordered (ky, kx, c), i.e. a [C][C][3][3] convolution weight permuted to
+ * [out][ky][kx][in]; ln*_g, ln*_b dev fp32 [C]; out dev bf16 [B][g*g][C]
+ * (token-major; SAM's channel-first tensor transposed).  C % 128 == 0 and
+ * D % 64 == 0 (else SSAM_EUNSUPPORTED). */
+size_t ssam_neck_workspace_bytes(int B, int g, int D, int C);
+int ssam_neck(const void *x, const void *w1, const float *ln1_g, const float *ln1_b,
+              const void *w2, const float *ln2_g, const float *ln2_b, float eps, void *out,
+              int B, int g, int D, int C, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,7 +50,8 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.ssam_status_string.restype = C.c_char_p
         for n in ("ssam_score_tokens_workspace_bytes", "ssam_routed_mlp_workspace_bytes",
-                  "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes", "ssam_linear_workspace_bytes"):
+                  "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes", "ssam_linear_workspace_bytes",
+                  "ssam_patch_embed_workspace_bytes", "ssam_neck_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         _lib = L
     return _lib
@@ -367,3 +368,50 @@ def ssam_encoder_forward(x, wstructs, is_global, cfg_local, cfg_global, window_t
         _f32(scores, "scores"), _i32(keep_idx, "keep_idx"),
         C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), qkv_events, _stream()))
     return x
+
+
+# ------------------------------------------------------------------ encoder ends
+def ssam_patch_embed_workspace_bytes(B, H, W, P) -> int:
+    return lib().ssam_patch_embed_workspace_bytes(C.c_int(B), C.c_int(H), C.c_int(W), C.c_int(P))
+
+
+def ssam_patch_embed(img, w, bias, pos, P, x=None, workspace=None):
+    """img [B,3,H,W] bf16; w [D,3*P*P] bf16; bias [D] fp32; pos [N,D] bf16 -> tokens [B,N,D] bf16."""
+    Bn, three, H, W = img.shape
+    D = w.shape[0]
+    N = (H // P) * (W // P)
+    assert three == 3 and w.shape[1] == 3 * P * P
+    if x is None:
+        x = torch.empty((Bn, N, D), dtype=torch.bfloat16, device=img.device)
+    if workspace is None:
+        workspace = torch.empty(ssam_patch_embed_workspace_bytes(Bn, H, W, P), dtype=torch.uint8, device=img.device)
+    _check("ssam_patch_embed", lib().ssam_patch_embed(
+        _bf(img, "img"), _bf(w, "w"), _f32(bias, "bias"), _bf(pos, "pos"), _bf(x, "x"), C.c_int(Bn), C.c_int(H), C.c_int(W),
+        C.c_int(P), C.c_int(D), C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return x
+
+
+def ssam_neck_workspace_bytes(B, g, D, Cn) -> int:
+    return lib().ssam_neck_workspace_bytes(C.c_int(B), C.c_int(g), C.c_int(D), C.c_int(Cn))
+
+
+def neck_conv3_weight(w2):
+    """[C,C,3,3] convolution weight (out, in, ky, kx) -> the [C, 9*C] layout of ssam_neck (out; ky, kx, in)."""
+    Cn = w2.shape[0]
+    return w2.permute(0, 2, 3, 1).reshape(Cn, 9 * Cn).contiguous()
+
+
+def ssam_neck(x, w1, ln1_g, ln1_b, w2, ln2_g, ln2_b, g, eps=1e-6, out=None, workspace=None):
+    """x [B,g*g,D] bf16; w1 [C,D]; w2 [C,9*C] (see neck_conv3_weight) -> [B,g*g,C] bf16."""
+    Bn, N, D = x.shape
+    Cn = w1.shape[0]
+    assert N == g * g and w2.shape == (Cn, 9 * Cn)
+    if out is None:
+        out = torch.empty((Bn, N, Cn), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(ssam_neck_workspace_bytes(Bn, g, D, Cn), dtype=torch.uint8, device=x.device)
+    _check("ssam_neck", lib().ssam_neck(
+        _bf(x, "x"), _bf(w1, "w1"), _f32(ln1_g, "ln1_g"), _f32(ln1_b, "ln1_b"), _bf(w2, "w2"), _f32(ln2_g, "ln2_g"),
+        _f32(ln2_b, "ln2_b"), C.c_float(eps), _bf(out, "out"), C.c_int(Bn), C.c_int(g), C.c_int(D), C.c_int(Cn),
+        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return out

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssam.so")
-SOURCES = ["tables.hip", "movers.hip", "gemm.hip", "attention.hip", "block.hip"]
+SOURCES = ["tables.hip", "movers.hip", "gemm.hip", "attention.hip", "block.hip", "ends.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
