@@ -205,13 +205,17 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 _Pragma("unroll") for (int j = 0; j < NT; ++j)                                        \
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], wf[ks_][j], acc[i][j], 0, 0, 0); \
         }
+        // A is requested 1.25 slabs before it is stored: the registers ra are stored to LDS in k-step 2 of a
+        // slab (data of the next slab, requested in k-step 3 of the previous one, so the store never waits for
+        // memory and completes a k-step before the barrier instead of right in front of it) and refilled in
+        // k-step 3 with the slab after next.
         GEMM_LOAD_GLOBAL_A(kb)
         GEMM_LOAD_W(kb, 0) GEMM_LOAD_W(kb, 1) GEMM_LOAD_W(kb, 2) GEMM_LOAD_W(kb, 3)
         GEMM_STORE_LDS_A(0)
+        GEMM_LOAD_GLOBAL_A(min(kb + 1, ke - 1))
         LDS_BARRIER();
         for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
             GEMM_LOAD_AFRAGS(buf, 0, 0)
-            GEMM_LOAD_GLOBAL_A(kt + 1)
             GEMM_LOAD_AFRAGS(buf, 1, 1)
             GEMM_MFMAS_W(0, 0)
             GEMM_LOAD_W(kt + 1, 0)
@@ -220,22 +224,23 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
             GEMM_LOAD_W(kt + 1, 1)
             GEMM_LOAD_AFRAGS(buf, 3, 1)
             GEMM_MFMAS_W(0, 2)
+            GEMM_STORE_LDS_A(buf ^ 1)
             GEMM_LOAD_W(kt + 1, 2)
             GEMM_MFMAS_W(1, 3)
+            GEMM_LOAD_GLOBAL_A(min(kt + 2, ke - 1))
             GEMM_LOAD_W(kt + 1, 3)
-            GEMM_STORE_LDS_A(buf ^ 1)
             GEMM_SGB(0x100, MT);
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); }
-            GEMM_SGB(0x020, NT);
-#pragma unroll
             for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
             GEMM_SGB(0x020, NT);
 #pragma unroll
             for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
             GEMM_SGB(0x020, NT);
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); }
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); }
+            GEMM_SGB(0x020, NT);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); }
             GEMM_SGB(0x020, NT);
             LDS_BARRIER();
         }
