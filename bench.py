@@ -569,6 +569,18 @@ def main():
                       f"({t_local:.2f} s each) and {len(glo)} global blocks ({t_global:.2f} s each), host-to-numpy weight "
                       f"conversion included; images/s extrapolated as 1/(t_sel + {shape.depth - n_glob}*t_local + {n_glob}*t_global)",
         }
+        # the whole ViT-B encoder on one image (the smallest full configuration), timed in full
+        if "other_models" in out:
+            sb = inputs.SHAPES["vit_b"]
+            rng_b = np.random.default_rng(args.seed + 500)
+            xb = inputs.token_field(rng_b, 1, g, sb.D)[0]
+            wb = inputs.encoder_weights(args.seed + 501, sb, g)
+            t0 = time.perf_counter()
+            oracle.encoder(xb, [oracle.BlockWeights(**w) for w in wb], sb.heads, sb.ws, sb.global_blocks, 4, r, rho)
+            tb = time.perf_counter() - t0
+            out["other_models"]["vit_b"]["cpu_oracle"] = {"images_per_s": round(1.0 / tb, 4), "seconds_per_image": round(tb, 2),
+                                                          "cores": out["cpu_baseline"]["cores"],
+                                                          "sample": "the whole encoder on one image, not extrapolated"}
     print(json.dumps(out))
 
 
