@@ -8,13 +8,28 @@ struct SplitWs { void *ptr; size_t bytes; };
 // How a launch of `total` large tiles over `slots` concurrent workgroups is cut: `rem` left-over large
 // tiles go to a second launch of `subs` smaller tiles each (0: none, when the tiles do not fill one
 // round, fill the last one exactly, or fill more than half of it), and that launch also cuts K into
-// `parts` ranges (1: no) when a workspace is there, K is long and the left-over is small.
+// `parts` ranges (1: no) when a workspace is there, K is long and the left-over is small.  A problem of less
+// than one round is treated as all left-over when cutting K gives it at least twice the workgroups.
 struct TailPlan { int rem, parts; };
 
 TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes, const SplitWs &ws)
 {
     TailPlan p = { total % slots, 1 };
-    if (total < slots || p.rem > slots / 2) p.rem = 0;
+    if (total < slots) {
+        // not even one round of large tiles (small batches): a handful of workgroups would each walk all of K
+        // alone.  With a workspace the whole problem runs as the left-over form instead: smaller tiles, K cut
+        // into ranges, so that about 512 workgroups share it.
+        const int n_all = total * subs;
+        int parts = nk / 4;
+        if (n_all > 0 && parts > 512 / n_all) parts = 512 / n_all;
+        if (ws.ptr && parts >= 2 && (size_t)n_all * parts * sub_tile_bytes <= ws.bytes) {
+            p.rem = total;
+            p.parts = parts;
+            return p;
+        }
+        p.rem = 0;
+    }
+    if (p.rem > slots / 2) p.rem = 0;
     if (p.rem == 0) return p;
     const int n_sub = p.rem * subs;
     int parts = nk / 4;                         // at least 4 slabs per workgroup
@@ -101,7 +116,7 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
 // one workgroup per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one
 // workgroup's epilogue behind the other's main loop); the
 // left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
-int pick_tile(int M, int N, int K, int epilogue, bool packed, const SplitWs &ws)
+int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
 {
     struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[4]; };   // t_epi: bias, +GELU, scatter-add, scatter
     const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
@@ -111,11 +126,11 @@ int pick_tile(int M, int N, int K, int epilogue, bool packed, const SplitWs &ws)
     int best = 3;
     double best_time = 1e30;
     for (const Cand &c : cands) {
-        if (N % c.bn != 0 || (packed && c.id == 2)) continue;
+        if (N % c.bn != 0 || c.id == 2) continue;    // 256x128 is never the fastest on these shapes: kept as a forced choice only
         const int subs = (c.bm / c.tm) * (c.bn / c.tn);
         const int total = ssam_div_up(M, c.bm) * (N / c.bn);
         const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
-        const double round = nk * c.t_slab * (packed ? 0.93 : 1.0) + c.t_epi[epilogue];
+        const double round = nk * c.t_slab + c.t_epi[epilogue];   // packed weights speed both tiles up alike: same choice, same sums
         double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
         if (plan.rem != 0) {
             const int n_sub = plan.rem * subs;
@@ -135,7 +150,7 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
     const SplitWs ws = { split_ws, split_ws_bytes };
     const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
     bf16 *c = (bf16 *)C;
-    if (tile == 0) tile = pick_tile(M, N, K, epilogue, packed, ws);
+    if (tile == 0) tile = pick_tile(M, N, K, epilogue, ws);
     if (packed) {
         switch (epilogue) {
         case SSAM_EPI_BIAS: return launch_tile_packed<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
