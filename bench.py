@@ -18,6 +18,7 @@ Extra legs (run after the timed region, reported inside the same JSON line):
   pixels_to_embedding  the whole image encoder: patch embedding, the blocks, the neck
   other_models  SAM ViT-B and ViT-L shaped encoders at batch 1 (sparse and dense)
   kernels_batch16  isolated global attention and routed MLP at batch 16 over densities 0.2 .. 1.0
+  hiera_l_routed_mlp  the routed MLP on the stage shapes of SAM2's Hiera-L encoder (shape-only)
   cpu_baseline  the CPU oracle on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -282,6 +283,51 @@ def sweep_leg(torch, hip, B, inputs, seed, reps=5):
     return out
 
 
+def hiera_leg(torch, hip, B, seed, Bn=4, reps=5):
+    """Residual-Consistency MLP on a second backbone (Sec. 5, SAM2 with the Hiera-L encoder): a shape-only leg.
+    Stage widths / token grids / block counts of Hiera-L on a 1024x1024 input (144, 288, 576, 1152 channels on
+    256^2, 128^2, 64^2, 32^2 tokens; 2, 6, 36, 4 blocks; MLP ratio 4) are the public architecture, not the paper's;
+    weights and tokens are random.  Per keep ratio r: the routed-MLP time of one image summed over all 48 blocks."""
+    dev = "cuda:0"
+    stages = [(256, 144, 2), (128, 288, 6), (64, 576, 36), (32, 1152, 4)]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    bf = torch.bfloat16
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = hip.event(), hip.event()
+    out = {"batch": Bn}
+    per_r = {}
+    for (g, D, blocks) in stages:
+        n, Dm = g * g, 4 * D
+        x = torch.randn((Bn, n, D), generator=gen, device=dev).to(bf)
+        scores = torch.exp(torch.randn((Bn, n), generator=gen, device=dev))
+        w = {"ln2_g": 1.0 + torch.randn(D, generator=gen, device=dev) * 0.02, "ln2_b": torch.randn(D, generator=gen, device=dev) * 0.02,
+             "w1": (torch.randn((Dm, D), generator=gen, device=dev) * 0.02).to(bf), "b1": torch.randn(Dm, generator=gen, device=dev) * 0.02,
+             "w2": (torch.randn((D, Dm), generator=gen, device=dev) * 0.02).to(bf), "b2": torch.randn(D, generator=gen, device=dev) * 0.02}
+        ws_buf = torch.empty(B.ssam_routed_mlp_workspace_bytes(Bn, n, D, Dm), dtype=torch.uint8, device=dev)
+        for r in (1.0, 0.7, 0.5, 0.3):
+            K = B.ssam_keep_count(n, r)
+            keep = B.ssam_select_tokens(scores, K)
+            fn = lambda: B.ssam_routed_mlp(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w["w1"], w["b1"], w["w2"], w["b2"], workspace=ws_buf)
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            hip.record(e0, stream)
+            for _ in range(reps):
+                fn()
+            hip.record(e1, stream)
+            torch.cuda.synchronize()
+            ms = hip.elapsed_ms(e0, e1) / reps
+            d = per_r.setdefault(r, {"ms_per_image": 0.0, "stages_us": []})
+            d["ms_per_image"] += ms * blocks / Bn
+            d["stages_us"].append(round(ms * 1e3, 1))
+        del x, scores, ws_buf
+    for r, d in per_r.items():
+        out["dense" if r == 1.0 else f"keep_{r}"] = {"mlp_ms_per_image": round(d["ms_per_image"], 3), "stage_call_us": d["stages_us"],
+                                                     "speedup_over_dense": round(per_r[1.0]["ms_per_image"] / d["ms_per_image"], 3)}
+    return out
+
+
 def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
     """The other encoder shapes the workload family names (SAM ViT-B / ViT-L, batch 1): images/s of the same
     path at each density and at density 1.0, packed weights, position-only order."""
@@ -539,6 +585,7 @@ def main():
         out["other_models"] = {"vit_b": model_leg(torch, B, inputs, "vit_b", 1, [0.4], 10, args.seed + 100),
                                "vit_l": model_leg(torch, B, inputs, "vit_l", 1, [0.3, 0.4], 10, args.seed + 200)}
         out["kernels_batch16"] = sweep_leg(torch, hip, B, inputs, args.seed + 300)
+        out["hiera_l_routed_mlp"] = hiera_leg(torch, hip, B, args.seed + 600)
 
     # ---- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:

@@ -124,7 +124,9 @@ typedef enum ssam_epilogue {
 } ssam_epilogue;
 
 /* C = epilogue(A W^T + bias).  A dev bf16 [M][K]; W dev bf16 [N][K]; bias dev
- * fp32 [N]; C dev bf16.  N % 128 == 0 and K % 64 == 0 (else SSAM_EUNSUPPORTED).
+ * fp32 [N]; C dev bf16.  N % 8 == 0 and K % 8 == 0 (else SSAM_EUNSUPPORTED;
+ * multiples of 128 / 64 are the fast case: a ragged last tile column or K slab
+ * is computed on clamped / zero operands and not stored).
  * SSAM_EPI_BIAS_SCATTER_ADD: row m = b*rows_per_batch + p of the product is
  * added into row b*dst_rows_per_batch + row_map[b*map_batch_stride + p] of C
  * (skipped where the map is negative); C holds the residual stream and is
@@ -171,7 +173,8 @@ int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed,
  * ignored) loads such fragments straight into registers and stages only A in
  * LDS, which halves its LDS traffic; results are bit-identical to the row-major
  * form.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 32 ==
- * 0 and K % 16 == 0 (else SSAM_EUNSUPPORTED); W and Wp must not overlap.  Tile
+ * 0 and K % 16 == 0 (else SSAM_EUNSUPPORTED; ssam_linear_ld takes packed
+ * weights only for N % 128 == 0 and K % 64 == 0); W and Wp must not overlap.  Tile
  * 2 (256x128) has no packed form (SSAM_EUNSUPPORTED when forced). */
 int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream);
 

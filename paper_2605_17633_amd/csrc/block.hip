@@ -85,7 +85,8 @@ static int routed_mlp_impl(void *x, const int32_t *keep_idx, const float *ln_g, 
     if (!x || !keep_idx || !ln_g || !ln_b || !w1 || !b1 || !w2 || !b2 || !workspace) return SSAM_EINVAL;
     if (B <= 0 || N <= 0 || D <= 0 || Dm <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
     if (!ssam_aligned16(workspace)) return SSAM_EINVAL;
-    if (D % 128 != 0 || Dm % 128 != 0) return SSAM_EUNSUPPORTED;
+    if (D % 8 != 0 || Dm % 8 != 0) return SSAM_EUNSUPPORTED;
+    if (packed && (D % 128 != 0 || Dm % 128 != 0)) return SSAM_EUNSUPPORTED;
     if (workspace_bytes < mlp_ws_bytes(B, K, D, Dm)) return SSAM_EWORKSPACE;
     unsigned char *ws = (unsigned char *)workspace;
     void *a2 = ws;

@@ -64,9 +64,9 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
 {
     constexpr int SUB_M = BM / TM, SUB_N = BN / TN;
     const GemmSplit whole = { nullptr, 1 };
-    GemmTileRange tr = { ssam_div_up(M, BM), N / BN, 0, 0 };
+    GemmTileRange tr = { ssam_div_up(M, BM), ssam_div_up(N, BN), 0, 0 };
     const int total = tr.tiles_m * tr.tiles_n;
-    const int nk = K / GEMM_BK;
+    const int nk = ssam_div_up(K, GEMM_BK);
     const TailPlan plan = plan_tail(total, slots, nk, SUB_M * SUB_N, (size_t)TM * TN * sizeof(float), ws);
     const int rem = plan.rem, parts = plan.parts;
     tr.tile_count = total - rem;
@@ -93,7 +93,7 @@ int launch_tile_packed(int tile, const bf16 *A, const bf16 *W, const float *bias
                        const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
     switch (tile) {
-    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI, 2, 4, true>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4, true>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI, 2, 2, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
     default: return SSAM_EUNSUPPORTED;
     }
@@ -104,7 +104,7 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
                 const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
     switch (tile) {
-    case 1: if (N % 256) return SSAM_EUNSUPPORTED; return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
+    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
     default: return SSAM_EINVAL;
@@ -122,13 +122,13 @@ int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
     const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
                             { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5, 4.5 } },
                             { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8, 4.0 } } };
-    const int nk = K / GEMM_BK;
+    const int nk = ssam_div_up(K, GEMM_BK);
     int best = 3;
     double best_time = 1e30;
     for (const Cand &c : cands) {
-        if (N % c.bn != 0 || c.id == 2) continue;    // 256x128 is never the fastest on these shapes: kept as a forced choice only
+        if (c.id == 2) continue;    // 256x128 is never the fastest on these shapes: kept as a forced choice only
         const int subs = (c.bm / c.tm) * (c.bn / c.tn);
-        const int total = ssam_div_up(M, c.bm) * (N / c.bn);
+        const int total = ssam_div_up(M, c.bm) * ssam_div_up(N, c.bn);
         const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
         const double round = nk * c.t_slab + c.t_epi[epilogue];   // packed weights speed both tiles up alike: same choice, same sums
         double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
@@ -203,9 +203,10 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, in
 {
     if (!A || !W || !bias || !C || M <= 0 || N <= 0 || K <= 0) return SSAM_EINVAL;
     if (!ssam_aligned16(A) || !ssam_aligned16(W) || !ssam_aligned16(bias) || !ssam_aligned16(C)) return SSAM_EINVAL;
+    if (N % 8 != 0 || K % 8 != 0) return SSAM_EUNSUPPORTED;
+    if (w_packed && (N % 128 != 0 || K % GEMM_BK != 0)) return SSAM_EUNSUPPORTED;
     if (lda < K || ldc < N || lda % 8 || ldc % 8 || (!w_packed && (ldw < K || ldw % 8))) return SSAM_EINVAL;
     if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
-    if (N % 128 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
     if (tile < 0 || tile > 3) return SSAM_EINVAL;
     if (w_packed && tile == 2) return SSAM_EUNSUPPORTED;
     GemmRowMap rm = { nullptr, 1, 0, 1 };

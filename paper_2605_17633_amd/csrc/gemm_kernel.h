@@ -52,6 +52,9 @@ __device__ __forceinline__ int gemm_swz(int row, int c) { return row * GEMM_BK +
 
 #define GEMM_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// 16 zero bytes: what a K chunk past the end of a ragged K reads instead of memory
+static __device__ const uint4 gemm_zero_chunk[1] = { { 0u, 0u, 0u, 0u } };
+
 struct GemmLd { int a, w, c; };   // row strides of A, W and C in elements (multiples of 8)
 
 struct GemmTileRange {
@@ -111,7 +114,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
     const int l32 = lane & 31, half = lane >> 5;
-    const int nk = K / GEMM_BK;
+    const int nk = (K + GEMM_BK - 1) / GEMM_BK;          // a ragged last slab reads zeros past K (K % 8 == 0)
     const int kb = (int)((long)nk * kpart / parts), ke = (int)((long)nk * (kpart + 1) / parts);   // this workgroup's slabs
 
     f32x16 acc[MT][NT];
@@ -131,17 +134,22 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i)          // rows past M repeat the last row; their results are never stored
         ga[i] = A + (long)min(m0 + r0 + RSTEP * i, M - 1) * ld.a + c0 * 8;
-    const bf16 *gb = W + (long)(n0 + r0) * ld.w + c0 * 8;
+    const bf16 *gb[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i)          // likewise columns past N (a ragged last tile column)
+        gb[i] = W + (long)min(n0 + r0 + RSTEP * i, N - 1) * ld.w + c0 * 8;
+    const bf16 *zchunk = reinterpret_cast<const bf16 *>(gemm_zero_chunk);
     const int lst = gemm_swz(r0, c0);          // + i*RSTEP*64: rows a multiple of 16 apart share the swizzle term
     const int fa0 = (wm + l32) * GEMM_BK, fb0 = (wn + l32) * GEMM_BK;
     const int sw = (l32 >> 1) & 7;
 
 #define GEMM_LOAD_GLOBAL(kt_)                                                                         \
     {                                                                                                 \
+        const bool kin_ = (kt_) * GEMM_BK + c0 * 8 < K;                                               \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                           \
-            ra[i] = *reinterpret_cast<const u32x4 *>(ga[i] + (kt_) * GEMM_BK);                        \
+            ra[i] = *reinterpret_cast<const u32x4 *>(kin_ ? ga[i] + (kt_) * GEMM_BK : zchunk);        \
         _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
-            rb[i] = *reinterpret_cast<const u32x4 *>(gb + (long)i * RSTEP * ld.w + (kt_) * GEMM_BK);        \
+            rb[i] = *reinterpret_cast<const u32x4 *>(kin_ ? gb[i] + (kt_) * GEMM_BK : zchunk);        \
     }
 #define GEMM_STORE_LDS(buf_)                                                                          \
     {                                                                                                 \
@@ -314,11 +322,12 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
         for (int e = 0; e < 8; ++e) bv[e] = 0.f;
     } else {
-        const float4 *b4 = reinterpret_cast<const float4 *>(bias + ncol);
+        const float4 *b4 = reinterpret_cast<const float4 *>(bias + (ncol < N ? ncol : 0));
         float4 x0 = b4[0], x1 = b4[1];
         bv[0] = x0.x; bv[1] = x0.y; bv[2] = x0.z; bv[3] = x0.w;
         bv[4] = x1.x; bv[5] = x1.y; bv[6] = x1.z; bv[7] = x1.w;
     }
+    const bool col_ok = ncol < N;               // N % 8 == 0: a lane's 8 columns are all inside or all outside
     // The scatter epilogue is a read-modify-write of rows of the residual stream.  Its destination rows
     // are looked up once per tile (one row per thread, parked in LDS behind the staging regions) and the
     // old values of a whole 32-row slice are requested before the slice is staged, so that the slice pays
@@ -348,7 +357,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
             for (int pass = 0; pass < PASSES; ++pass) {
                 drow[pass] = dst_row[wm + i * 32 + pass * RPP + rl];
-                if (EPI == SSAM_EPI_BIAS_SCATTER_ADD && drow[pass] >= 0)
+                if (EPI == SSAM_EPI_BIAS_SCATTER_ADD && drow[pass] >= 0 && col_ok)
                     old[pass] = *reinterpret_cast<const uint4 *>(C + (long)drow[pass] * ld.c + ncol);
             }
         }
@@ -363,7 +372,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         for (int pass = 0; pass < PASSES; ++pass) {
             const int row = pass * RPP + rl;
             const int m = m0 + wm + i * 32 + row;
-            if (m >= M) continue;
+            if (m >= M || (EPI != GEMM_EPI_PARTIAL && !col_ok)) continue;
             const float4 *s4 = reinterpret_cast<const float4 *>(stage + row * EPS + cl * 8);
             float4 y0 = s4[0], y1 = s4[1];
             if (EPI == GEMM_EPI_PARTIAL) {
@@ -410,7 +419,7 @@ gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const floa
     int m0, n0;
     gemm_tile_origin(tr, tr.tile_begin + slot / SUBS, slot % SUBS, SUB_M, SUB_N, BM, BN, m0, n0);
     const int m = m0 + row, ncol = n0 + col;
-    if (m >= M) return;
+    if (m >= M || ncol >= N) return;
     float v[8];
     {
         const float4 *b4 = reinterpret_cast<const float4 *>(bias + ncol);

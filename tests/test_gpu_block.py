@@ -117,7 +117,8 @@ def test_attention_rejects_unsupported():
 
 
 # ------------------------------------------------------------------ routed MLP
-@pytest.mark.parametrize("B_,n,D,Dm,rho", [(2, 784, 768, 3072, 0.4), (1, 500, 128, 256, 0.3), (1, 300, 1280, 5120, 1.0)])
+@pytest.mark.parametrize("B_,n,D,Dm,rho", [(2, 784, 768, 3072, 0.4), (1, 500, 128, 256, 0.3), (1, 300, 1280, 5120, 1.0),
+                                           (2, 1024, 144, 576, 0.5), (1, 700, 288, 1152, 0.3)])   # the last two: hierarchical-encoder widths
 def test_routed_mlp(B_, n, D, Dm, rho):
     announce("routed_mlp", B_, n, D, Dm, rho)
     rng = np.random.default_rng(20)

@@ -308,6 +308,36 @@ def test_linear_every_instantiation(tile, M, N, K, epi, packed):
         assert_close(to_np(out), want, f"tile{tile} epi{epi}", tol=1e-2)
 
 
+@pytest.mark.parametrize("epi", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile,M,N,K", [(0, 500, 144, 576), (0, 1000, 576, 144), (3, 333, 288, 1152), (1, 700, 1160, 200),
+                                        (0, 70000, 144, 576), (1, 8400, 2056, 1096), (3, 4200, 2056, 1096)])
+def test_linear_ragged_widths(tile, M, N, K, epi):
+    """N and K that are multiples of 8 only (the stage widths of hierarchical encoders: 144, 288, 576):
+    ragged last tile column and ragged last K slab, every epilogue, single, left-over and K-split launches."""
+    announce("linear ragged", tile, M, N, K, epi)
+    A, W, b, ref, Ad, Wd, bd = _sweep_case(M, N, K)
+    ws = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    if epi in (2, 3):
+        rows_out = M + 5
+        dst = np.random.default_rng(3).permutation(rows_out)[:M].astype(np.int32)
+        x = inputs.bf16_round(np.random.default_rng(4).normal(size=(rows_out, N)).astype(np.float32))
+        out = dev_bf16(x)
+        B.ssam_linear_ld(Ad, Wd, bd, out, epilogue=epi, row_map=dev_i32(dst), rows_per_batch=M, map_batch_stride=0,
+                         dst_rows_per_batch=rows_out, tile=tile, workspace=ws)
+        got = to_np(out)
+        want = ref + x[dst] if epi == 2 else ref
+        assert_close(got[dst], want, f"ragged tile{tile} epi{epi}", tol=1e-2)
+        rest = np.setdiff1d(np.arange(rows_out), dst)
+        assert np.array_equal(got[rest].view(np.uint32), x[rest].view(np.uint32))
+    else:
+        # the result sits in a wider buffer: the columns past N must stay untouched
+        buf = torch.full((M, N + 24), 3.0, dtype=torch.bfloat16, device=DEV)
+        B.ssam_linear_ld(Ad, Wd, bd, buf[:, :N], epilogue=epi, tile=tile, workspace=ws)
+        want = torch.nn.functional.gelu(torch.from_numpy(ref)).numpy() if epi == 1 else ref
+        assert_close(to_np(buf[:, :N]), want, f"ragged tile{tile} epi{epi}", tol=1e-2)
+        assert bool((buf[:, N:] == 3.0).all())
+
+
 def test_linear_row_strides():
     """Operands and result as column slices of wider buffers: strides are honoured, padding untouched."""
     announce("linear strides")
@@ -357,9 +387,9 @@ def test_linear_scatter_add(tile):
 
 
 def test_linear_rejects_unsupported():
-    A = torch.zeros((8, 48), dtype=torch.bfloat16, device=DEV)
-    W = torch.zeros((128, 48), dtype=torch.bfloat16, device=DEV)
-    b = torch.zeros(128, device=DEV)
+    A = torch.zeros((8, 64), dtype=torch.bfloat16, device=DEV)
+    W = torch.zeros((100, 64), dtype=torch.bfloat16, device=DEV)          # N not a multiple of 8
+    b = torch.zeros(100, device=DEV)
     with pytest.raises(B.SsamError) as e:
         B.ssam_linear(A, W, b)
     assert e.value.code == B.EUNSUPPORTED
