@@ -118,16 +118,53 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
     }
 }
 
+// Window form of the bias tables.  A window has 2w-1 <= 32 relative positions, so rel x Q^T is one MFMA tile
+// per table and is stored the way it leaves the matrix core, query-major and without predicates:
+//   tq[q*WIN_TSTR + m]                 = log2e * q . rel_h[m]
+//   tq[(32 + q)*WIN_TSTR + m]          = log2e * q . rel_w[m]        (m = 0..31; rows past 2w-2 of rel are zero)
+// A key in row kr, column kc is then entry qrow - kr + w - 1 of the first and qcol - kc + w - 1 of the second
+// row of the lane's query.  Entries are fp16 (see GlbTab); the row stride keeps the 8-byte stores aligned.
+typedef _Float16 WinTab;
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+constexpr int WIN_TSTR = 36;
+template <int D>
+__device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr, WinTab *tq)
+{
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int tab = 0; tab < 2; ++tab) {
+        const bf16 *rel = (tab ? rel_w : rel_h) + l32 * rstr + half * 8;
+        f32x16 u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) u[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < AttnCfg<D>::KS; ++ks)
+            u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(rel + ks * 16), qf[ks], u, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");          // MFMA passes done before u is read (as in build_bias_rows)
+        __builtin_amdgcn_sched_barrier(0);
+        WinTab *dst = tq + (tab * 32 + l32) * WIN_TSTR + 4 * half;    // u[4g + e] is rel row 8g + 4*half + e of query l32
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f16x4 hv = { (_Float16)(u[4 * g] * LOG2E), (_Float16)(u[4 * g + 1] * LOG2E),
+                         (_Float16)(u[4 * g + 2] * LOG2E), (_Float16)(u[4 * g + 3] * LOG2E) };
+            *reinterpret_cast<f16x4 *>(dst + 8 * g) = hv;
+        }
+    }
+}
+
 // A chunk of nb (1..NB, wave-uniform) 32-key blocks against the wave's 32 queries.
 //   Ks, Vs: LDS, row-major rows ([keys][KSTR]); blk[b]: index of the chunk's b-th block in them
-//   krc:    LDS, per key the byte offsets of its two entries in the wave's entry-major bias tables:
-//           low half = 32*esz*row, high half = 32*esz*(ts + col); indexed like Ks
+//   krc:    LDS, per key two byte offsets into the bias tables, indexed like Ks: low half for the row part,
+//           high half for the column part (entry-major tables: 32*esz*row and 32*esz*(ts + col); window
+//           tables: the key's share of the entry index, see key_bias_offsets_window)
 //   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
-//   tq:     the wave's bias tables at this lane's query (entry p at tq[32*p])
+//   tq_h, tq_w: where this lane's query starts in the row-part and column-part bias tables; a key's two
+//           bias terms are read at tq_h + (low half of krc) and tq_w + (high half of krc), in bytes
 template <int D, int NB, bool RAGGED, typename TabT>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
-                                                int S, float scale_log2e, const TabT *tq)
+                                                int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
 {
     using C = AttnCfg<D>;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
@@ -153,7 +190,8 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (b < nb) {
-            const unsigned char *tqb = reinterpret_cast<const unsigned char *>(tq);
+            const unsigned char *tqh = reinterpret_cast<const unsigned char *>(tq_h);
+            const unsigned char *tqw = reinterpret_cast<const unsigned char *>(tq_w);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const u32x4 rc = *reinterpret_cast<const u32x4 *>(krc + blk[b] * 32 + 8 * g + 4 * half);
@@ -161,8 +199,8 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * g + e;
                     const uint32_t c = rc[e];
-                    const float bh = (float)*reinterpret_cast<const TabT *>(tqb + (c & 0xffffu));
-                    const float bw = (float)*reinterpret_cast<const TabT *>(tqb + (c >> 16));
+                    const float bh = (float)*reinterpret_cast<const TabT *>(tqh + (c & 0xffffu));
+                    const float bw = (float)*reinterpret_cast<const TabT *>(tqw + (c >> 16));
                     float val = s[b][r] * scale_log2e + bh + bw;
                     if (RAGGED) val = (key0[b] + 8 * g + 4 * half + e < S) ? val : -INFINITY;
                     s[b][r] = val;
@@ -287,6 +325,14 @@ __device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p
     return (32u * esz * (rc & 0xffffu)) | ((32u * esz * ((uint32_t)ts + (rc >> 16))) << 16);
 }
 
+// window kernel: byte offsets of the key's entries within a query's two table rows, less the query's own part
+__device__ __forceinline__ uint32_t key_bias_offsets_window(const int32_t *sigma, int p, int S, int w)
+{
+    uint32_t rc = key_row_col(sigma, p, S, w);
+    const uint32_t esz = sizeof(WinTab);
+    return (esz * (uint32_t)(w - 1 - (int)(rc & 0xffffu))) | ((esz * (uint32_t)(w - 1 - (int)(rc >> 16))) << 16);
+}
+
 // per-wave LDS scratch: the bias rows of its 32 queries, later overlaid by its output staging tile
 template <int D>
 __host__ __device__ inline int wave_scratch_bytes(int ts, int esz = 4)
@@ -299,11 +345,18 @@ __host__ __device__ inline int wave_scratch_bytes(int ts, int esz = 4)
 inline int window_rel_rows(int w) { return ((2 * w - 1 + 31) / 32) * 32; }
 
 template <int D>
+__host__ __device__ inline int window_scratch_bytes()
+{
+    int bias = 2 * 32 * WIN_TSTR * (int)sizeof(WinTab), stage = 32 * AttnCfg<D>::KSTR * 2;
+    return ((bias > stage ? bias : stage) + 15) & ~15;
+}
+
+template <int D>
 size_t window_lds_bytes(int nqb, int w)
 {
-    int SP = nqb * 32, ts = w | 1;
+    int SP = nqb * 32;
     return (size_t)2 * SP * AttnCfg<D>::KSTR * 2 + (size_t)2 * window_rel_rows(w) * AttnCfg<D>::KSTR * 2 +
-           (size_t)nqb * wave_scratch_bytes<D>(ts) + (size_t)SP * 4;
+           (size_t)nqb * window_scratch_bytes<D>() + (size_t)SP * 4;
 }
 
 constexpr int WIN_NB = 2;            // key blocks per softmax chunk in the window kernel (register budget: 2 waves per SIMD)
@@ -315,14 +368,14 @@ attn_window_kernel(AttnParams P, int n_groups)
 {
     using C = AttnCfg<D>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int nqb = blockDim.x >> 6, SP = nqb * 32, ts = P.w | 1;
-    const int nrel = 2 * P.w - 1, rrows = ((nrel + 31) / 32) * 32;
+    const int nqb = blockDim.x >> 6, SP = nqb * 32;
+    const int nrel = 2 * P.w - 1, rrows = ((nrel + 31) / 32) * 32;      // nrel <= 32 (checked on the host)
     bf16 *Ks = reinterpret_cast<bf16 *>(smem);
     bf16 *Vs = Ks + SP * C::KSTR;
     bf16 *Rh = Vs + SP * C::KSTR;                 // rel-pos tables, zero-padded to rrows rows
     bf16 *Rw = Rh + rrows * C::KSTR;
     unsigned char *T = reinterpret_cast<unsigned char *>(Rw + rrows * C::KSTR);
-    const int wsb = wave_scratch_bytes<D>(ts);
+    const int wsb = window_scratch_bytes<D>();
     uint32_t *krc = reinterpret_cast<uint32_t *>(T + nqb * wsb);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31;
@@ -331,7 +384,7 @@ attn_window_kernel(AttnParams P, int n_groups)
 
     // problem-independent state: scan-order geometry and the rel-pos tables
     if (P.sigma_stride == 0)
-        for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(P.sigma, p, S, P.w, ts);
+        for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets_window(P.sigma, p, S, P.w);
     for (int id = tid; id < 2 * rrows * C::CH; id += blockDim.x) {
         int tab = id / (rrows * C::CH), rem = id % (rrows * C::CH), row = rem / C::CH, c = rem % C::CH;
         u32x4 v = { 0, 0, 0, 0 };
@@ -341,26 +394,33 @@ attn_window_kernel(AttnParams P, int n_groups)
     const int q0 = wave * 32, qpos = q0 + l32;
     const int qclamp = qpos < S ? qpos : S - 1;
     uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
-    float *tq = reinterpret_cast<float *>(T + wave * wsb);
+    WinTab *tq = reinterpret_cast<WinTab *>(T + wave * wsb);
     const int nact = P.n_pre + (wave >= P.n_pre ? 1 : 0);
 
     u32x4 rk[WIN_MAX_LOADS], rv[WIN_MAX_LOADS];
     bf16x8 qf[C::KS], qnext[C::KS];
 
-#define WIN_PREFETCH(prob_)                                                                             \
+    // The next problem's operands are requested in three pieces (K, V, Q) spread over the current problem's
+    // phases: a CU keeps only so many cache-line requests in flight, and a wave that issues all of its loads
+    // at once sits in the issue queue behind the other waves' loads instead of computing.
+#define WIN_PREFETCH(prob_, WHAT)                                                                       \
     {                                                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
         const int g_ = (prob_) / P.h, hd_ = (prob_) % P.h;                                              \
         const long base_ = (long)g_ * S * P.row_stride + (long)hd_ * D;                                 \
-        _Pragma("unroll") for (int i = 0; i < WIN_MAX_LOADS; ++i)                                       \
-        {                                                                                               \
-            int id = tid + i * (int)blockDim.x, key = id / C::CH, c = id % C::CH;                       \
-            key = key < S ? key : S - 1; /* pad keys repeat the last row: finite values, masked */      \
-            if (i < nloads) {                                                                           \
-                rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base_ + (long)key * P.row_stride + c * 8); \
-                rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base_ + (long)key * P.row_stride + c * 8); \
+        if ((WHAT) & 3) {                                                                               \
+            _Pragma("unroll") for (int i = 0; i < WIN_MAX_LOADS; ++i)                                   \
+            {                                                                                           \
+                int id = tid + i * (int)blockDim.x, key = id / C::CH, c = id % C::CH;                   \
+                key = key < S ? key : S - 1; /* pad keys repeat the last row: finite values, masked */  \
+                if (i < nloads && ((WHAT) & 1))                                                         \
+                    rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base_ + (long)key * P.row_stride + c * 8); \
+                if (i < nloads && ((WHAT) & 2))                                                         \
+                    rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base_ + (long)key * P.row_stride + c * 8); \
             }                                                                                           \
         }                                                                                               \
-        load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);                              \
+        if ((WHAT) & 4) load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
     }
 
     // Problems are dealt so that the heads of one window run on one XCD (workgroup b sits on XCD b & 7):
@@ -370,7 +430,7 @@ attn_window_kernel(AttnParams P, int n_groups)
     auto local_problem = [&](int lp) { int g = xcd + 8 * (lp / P.h); return g < n_groups ? g * P.h + lp % P.h : -1; };
     int lp = blockIdx.x >> 3;
     int prob = local_problem(lp);
-    if (prob >= 0) WIN_PREFETCH(prob)
+    if (prob >= 0) WIN_PREFETCH(prob, 7)
     for (; prob >= 0; lp += nslots, prob = local_problem(lp)) {
         const int grp = prob / P.h, head = prob % P.h;
         long my_row = -1;                         // output row of this lane's query, looked up long before it is needed
@@ -389,18 +449,22 @@ attn_window_kernel(AttnParams P, int n_groups)
         }
         if (P.sigma_stride != 0) {                // per-group order: this window's own sigma
             const int32_t *sg = P.sigma + (long)grp * P.sigma_stride;
-            for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets(sg, p, S, P.w, ts);
+            for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets_window(sg, p, S, P.w);
             qrc = key_row_col(sg, qclamp, S, P.w);
         }
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) qf[ks] = qnext[ks];
-        if (local_problem(lp + nslots) >= 0) WIN_PREFETCH(local_problem(lp + nslots))
-        build_bias_rows<D, float>(qf, Rh, Rw, C::KSTR, true, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+        const int next = local_problem(lp + nslots);
+        if (next >= 0) WIN_PREFETCH(next, 1)
+        build_bias_rows_window<D>(qf, Rh, Rw, C::KSTR, tq);
+        const WinTab *tq_h = tq + l32 * WIN_TSTR + (int)(qrc & 0xffffu);            // this lane's query in the two tables
+        const WinTab *tq_w = tq + (32 + l32) * WIN_TSTR + (int)(qrc >> 16);
         LDS_BARRIER();
+        if (next >= 0) WIN_PREFETCH(next, 2)
 
         WaveState<D> st;
         init_state<D>(st);
-        // active key tiles of query tile `wave`: the dense prefix, then the diagonal; chunks of four
+        // active key tiles of query tile `wave`: the dense prefix, then the diagonal; chunks of WIN_NB
         for (int a0 = 0; a0 < nact; a0 += WIN_NB) {
             int blk[WIN_NB], key0[WIN_NB];
 #pragma unroll
@@ -414,10 +478,11 @@ attn_window_kernel(AttnParams P, int n_groups)
 #pragma unroll
             for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
             if (ragged)
-                attn_chunk_step<D, WIN_NB, true, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32);
+                attn_chunk_step<D, WIN_NB, true, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq_h, tq_w);
             else
-                attn_chunk_step<D, WIN_NB, false, float>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq + l32);
+                attn_chunk_step<D, WIN_NB, false, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq_h, tq_w);
         }
+        if (next >= 0) WIN_PREFETCH(next, 4)
         finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
     }
 }
@@ -521,9 +586,9 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             for (int b = 0; b < GLB_NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
             const int nb = min(GLB_NB, nblk - c0);
             if (key0[GLB_NB - 1] + 32 > S)
-                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32);
+                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             else
-                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32);
+                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
         }
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
@@ -541,6 +606,7 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return SSAM_EHIP;
         if (ssam_div_up((long)nqb * 32 * AttnCfg<D>::CH, nqb * 64) > WIN_MAX_LOADS) return SSAM_EUNSUPPORTED;
+        if (2 * P.w - 1 > 32) return SSAM_EUNSUPPORTED;       // the window bias tables are one 32-row MFMA tile
         int n_problems = groups * P.h;
         // persistent workgroups: as many as fit on the 256 CUs at once for this LDS footprint
         int per_cu = (int)((160 * 1024) / lds);
