@@ -78,31 +78,37 @@ __device__ __forceinline__ void init_state(WaveState<D> &st)
 // that look up the same key (a key's row and column are the same for every query) hit consecutive banks:
 //   tq[p*32 + q]        = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
 //   tq[(ts + p)*32 + q] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
-// rel tables: rows of `rstr` elements, from global memory (rstr = D) or from a zero-padded LDS copy.
+// rel tables: rows of `rstr` elements in global memory.
 template <int D, typename TabT>
 __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr,
-                                                bool rows_padded, int w, int qrow, int qcol,
-                                                TabT *tq, int ts)
+                                                int w, int qrow, int qcol, TabT *tq, int ts)
 {
+    constexpr int KS = AttnCfg<D>::KS;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int nrel = 2 * w - 1;
+    // operand a of slab mt: rows mt*32 + l32 of both tables; rows past the table re-read its last row (their
+    // products are never stored), so every load is unconditional and a slab's 2*KS loads are in flight together
+    bf16x8 cur[2][KS], nxt[2][KS];
+    auto load_slab = [&](bf16x8 (&a)[2][KS], int mt) {
+        const int mrow = min(mt * 32 + l32, nrel - 1);
+#pragma unroll
+        for (int tab = 0; tab < 2; ++tab)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                a[tab][ks] = *reinterpret_cast<const bf16x8 *>((tab ? rel_w : rel_h) + (long)mrow * rstr + ks * 16 + half * 8);
+    };
+    load_slab(cur, 0);
     for (int mt = 0; mt * 32 < nrel; ++mt) {
+        // requested before this slab's products, used after them; past the last slab it re-reads the last row:
+        // an unconditional request keeps the wait below counted (a branch here would force a full drain)
+        load_slab(nxt, mt + 1);
 #pragma unroll
         for (int tab = 0; tab < 2; ++tab) {
-            const bf16 *rel = tab ? rel_w : rel_h;
             f32x16 u;
 #pragma unroll
             for (int r = 0; r < 16; ++r) u[r] = 0.f;
-            const int mrow = mt * 32 + l32;
-            const bool ok = rows_padded || mrow < nrel;
 #pragma unroll
-            for (int ks = 0; ks < AttnCfg<D>::KS; ++ks) {
-                bf16x8 a;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] = (bf16)0.f;
-                if (ok) a = *reinterpret_cast<const bf16x8 *>(rel + (long)mrow * rstr + ks * 16 + half * 8);
-                u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], u, 0, 0, 0);
-            }
+            for (int ks = 0; ks < KS; ++ks) u = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[tab][ks], qf[ks], u, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");          // MFMA passes done before u is read under predicates
             __builtin_amdgcn_sched_barrier(0);
@@ -115,6 +121,10 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
                 if (p >= 0 && p < w && m < nrel) dst[p * 32] = (TabT)(u[r] * LOG2E);
             }
         }
+#pragma unroll
+        for (int tab = 0; tab < 2; ++tab)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) cur[tab][ks] = nxt[tab][ks];
     }
 }
 
@@ -311,17 +321,21 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
     }
 }
 
-__device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int S, int w)
+__device__ __forceinline__ uint32_t cell_row_col(int cell, int w)
 {
-    int cell = sigma[p < S ? p : S - 1];
     cell = min(max(cell, 0), w * w - 1);
     return (uint32_t)(cell / w) | ((uint32_t)(cell % w) << 16);
 }
 
-// the same as byte offsets of the key's two entries in the wave's entry-major bias tables (row part, then column part)
-__device__ __forceinline__ uint32_t key_bias_offsets(const int32_t *sigma, int p, int S, int w, int ts, uint32_t esz = 4u)
+__device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int S, int w)
 {
-    uint32_t rc = key_row_col(sigma, p, S, w);
+    return cell_row_col(sigma[p < S ? p : S - 1], w);
+}
+
+// byte offsets of a cell's two entries in the wave's entry-major bias tables (row part, then column part)
+__device__ __forceinline__ uint32_t cell_bias_offsets(int cell, int w, int ts, uint32_t esz)
+{
+    uint32_t rc = cell_row_col(cell, w);
     return (32u * esz * (rc & 0xffffu)) | ((32u * esz * ((uint32_t)ts + (rc >> 16))) << 16);
 }
 
@@ -399,6 +413,7 @@ attn_window_kernel(AttnParams P, int n_groups)
 
     u32x4 rk[WIN_MAX_LOADS], rv[WIN_MAX_LOADS];
     bf16x8 qf[C::KS], qnext[C::KS];
+    int32_t row_next = -1;
 
     // The next problem's operands are requested in three pieces (K, V, Q) spread over the current problem's
     // phases: a CU keeps only so many cache-line requests in flight, and a wave that issues all of its loads
@@ -419,6 +434,7 @@ attn_window_kernel(AttnParams P, int n_groups)
                     rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base_ + (long)key * P.row_stride + c * 8); \
             }                                                                                           \
         }                                                                                               \
+        if (((WHAT) & 1) && P.out_rows != nullptr && qpos < S) row_next = P.out_rows[(long)g_ * S + qpos]; \
         if ((WHAT) & 4) load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);              \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
@@ -433,11 +449,8 @@ attn_window_kernel(AttnParams P, int n_groups)
     if (prob >= 0) WIN_PREFETCH(prob, 7)
     for (; prob >= 0; lp += nslots, prob = local_problem(lp)) {
         const int grp = prob / P.h, head = prob % P.h;
-        long my_row = -1;                         // output row of this lane's query, looked up long before it is needed
-        if (qpos < S) {
-            my_row = (long)grp * S + qpos;
-            if (P.out_rows) my_row = P.out_rows[my_row];
-        }
+        long my_row = -1;                         // output row of this lane's query (a mapped row was requested a problem ahead)
+        if (qpos < S) my_row = P.out_rows ? (long)row_next : (long)grp * S + qpos;
         LDS_BARRIER();                            // every wave is done with the previous problem's LDS (output stores stay in flight)
 #pragma unroll
         for (int i = 0; i < WIN_MAX_LOADS; ++i) {
@@ -541,19 +554,23 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
 
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
     u32x4 rk[LOADS], rv[LOADS];
-    uint32_t rrc = 0;
+    int rcell = 0;
 
-#define ATTN_LOAD_TILE(kt_)                                                                             \
+    // WHAT: 1 = K and the keys' cells, 2 = V; the two halves are requested at different points of the
+    // current tile's work so that the waves do not queue up behind each other's loads
+#define ATTN_LOAD_TILE(kt_, WHAT)                                                                       \
     {                                                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
         const int key0_ = (kt_) * GLB_TILE;                                                             \
         _Pragma("unroll") for (int i = 0; i < LOADS; ++i)                                               \
         {                                                                                               \
             int id = tid + i * 256, key = key0_ + id / C::CH, c = id % C::CH;                           \
             key = key < S ? key : S - 1; /* keys past S repeat the last row; masked in the scores */   \
-            rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8);    \
-            rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8);    \
+            if ((WHAT) & 1) rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8); \
+            if ((WHAT) & 2) rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8); \
         }                                                                                               \
-        if (tid < GLB_TILE) rrc = key_bias_offsets(sg, key0_ + tid, S, P.w, ts, sizeof(GlbTab));        \
+        if (((WHAT) & 1) && tid < GLB_TILE) rcell = sg[min(key0_ + tid, S - 1)]; /* used at the LDS store, not before */ \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
     }
 #define ATTN_STORE_TILE()                                                                               \
     {                                                                                                   \
@@ -563,11 +580,11 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = rk[i];                             \
             *reinterpret_cast<u32x4 *>(Vs + key * C::KSTR + c * 8) = rv[i];                             \
         }                                                                                               \
-        if (tid < GLB_TILE) krc[tid] = rrc;                                                             \
+        if (tid < GLB_TILE) krc[tid] = cell_bias_offsets(rcell, P.w, ts, sizeof(GlbTab));              \
     }
 
-    ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt)          // in flight while the bias rows are formed
-    build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, false, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+    ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt, 3)       // in flight while the bias rows are formed
+    build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
 
     WaveState<D> st;
     init_state<D>(st);
@@ -576,7 +593,8 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
         LDS_BARRIER();                         // every wave is done with the previous tile
         ATTN_STORE_TILE()
         LDS_BARRIER();
-        if (a + 1 < nact) ATTN_LOAD_TILE(a + 1 < P.n_pre ? a + 1 : qt)
+        const int kt_next = a + 1 < P.n_pre ? a + 1 : qt;
+        if (a + 1 < nact) ATTN_LOAD_TILE(kt_next, 1)
         const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
 #pragma unroll
         for (int c0 = 0; c0 < GLB_TILE / 32; c0 += GLB_NB) {
@@ -589,6 +607,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
                 attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             else
                 attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+            if (c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
         }
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
