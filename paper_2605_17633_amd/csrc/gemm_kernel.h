@@ -346,21 +346,31 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
         if (tid < BM) dst_row[tid] = mine;
     }
     __syncthreads();                            // pipeline buffers free for staging; dst_row visible
+    // The bias values must have landed before the first store pass: a pass that first touched them behind its
+    // row predicate would wait with a full drain of the memory counter, which on this hardware also counts the
+    // stores of the passes before it, and every pass would then wait for the previous pass's store to complete.
+#pragma unroll
+    for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(bv[e]));
     // From here on a wave touches only its own staging region: LDS operations of one wave execute in
     // order, so the slices need no workgroup barrier (which would also wait for the previous slice's
     // global stores); wavefront fences keep the compiler from reordering the LDS accesses.
+    // Destination rows and old values of a 32-row slice.  The loads are unconditional (a skipped row or column
+    // reads row 0 / column 0 and drops the value: loads behind a predicate would each be waited for on their own)
+    // and a slice's loads are issued before the stores of the slice before it, so the wait for them (a count
+    // of younger operations still allowed in flight) does not wait for those stores to complete.
+    uint4 old[PASSES], old_next[PASSES];
+    int drow[PASSES], drow_next[PASSES];
+    auto preload_slice = [&](int i, uint4 (&o)[PASSES], int (&d)[PASSES]) {
+#pragma unroll
+        for (int pass = 0; pass < PASSES; ++pass) {
+            d[pass] = dst_row[wm + i * 32 + pass * RPP + rl];
+            if (EPI == SSAM_EPI_BIAS_SCATTER_ADD)
+                o[pass] = *reinterpret_cast<const uint4 *>(C + (long)max(d[pass], 0) * ld.c + (col_ok ? ncol : 0));
+        }
+    };
+    if (MAPPED) preload_slice(0, old, drow);
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-        uint4 old[PASSES];
-        int drow[PASSES];
-        if (MAPPED) {
-#pragma unroll
-            for (int pass = 0; pass < PASSES; ++pass) {
-                drow[pass] = dst_row[wm + i * 32 + pass * RPP + rl];
-                if (EPI == SSAM_EPI_BIAS_SCATTER_ADD && drow[pass] >= 0 && col_ok)
-                    old[pass] = *reinterpret_cast<const uint4 *>(C + (long)drow[pass] * ld.c + ncol);
-            }
-        }
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -368,6 +378,12 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                 stage[(8 * (r >> 2) + 4 * half + (r & 3)) * EPS + j * 32 + l32] = acc[i][j][r];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (MAPPED && i + 1 < MT) preload_slice(i + 1, old_next, drow_next);
+        if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {   // this slice's old values, waited for once (see the bias values above)
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass)
+                asm volatile("" : "+v"(old[pass].x), "+v"(old[pass].y), "+v"(old[pass].z), "+v"(old[pass].w));
+        }
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int row = pass * RPP + rl;
@@ -401,6 +417,10 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // the slice is read before the next one is staged
+        if (MAPPED && i + 1 < MT) {
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) { old[pass] = old_next[pass]; drow[pass] = drow_next[pass]; }
+        }
     }
 }
 
