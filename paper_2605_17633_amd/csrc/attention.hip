@@ -171,12 +171,14 @@ __device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const b
 //   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
 //   tq_h, tq_w: where this lane's query starts in the row-part and column-part bias tables; a key's two
 //           bias terms are read at tq_h + (low half of krc) and tq_w + (high half of krc), in bytes
-template <int D, int NB, bool RAGGED, typename TabT>
+//   FULL:   the chunk has all NB blocks (nb is not looked at: no per-block branches, no dummy scores)
+template <int D, int NB, bool RAGGED, bool FULL, typename TabT>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
-                                                const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
+                                                const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb_,
                                                 int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
 {
     using C = AttnCfg<D>;
+    const int nb = FULL ? NB : nb_;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     f32x16 s[NB];
 #pragma unroll
@@ -234,7 +236,7 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
         }
     }
     st.l = st.l * alpha + psum;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {       // the running maximum moved for some query
+    {
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -264,6 +266,20 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
                 }
             }
         }
+    }
+}
+
+template <int D, int NB, typename TabT>
+__device__ __forceinline__ void attn_chunk(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
+                                           const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb,
+                                           bool ragged, int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
+{
+    if (nb == NB) {
+        if (ragged) attn_chunk_step<D, NB, true, true, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        else attn_chunk_step<D, NB, false, true, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+    } else {
+        if (ragged) attn_chunk_step<D, NB, true, false, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        else attn_chunk_step<D, NB, false, false, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
     }
 }
 
@@ -490,10 +506,7 @@ attn_window_kernel(AttnParams P, int n_groups)
             bool ragged = false;
 #pragma unroll
             for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
-            if (ragged)
-                attn_chunk_step<D, WIN_NB, true, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq_h, tq_w);
-            else
-                attn_chunk_step<D, WIN_NB, false, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), S, P.scale_log2e, tq_h, tq_w);
+            attn_chunk<D, WIN_NB, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), ragged, S, P.scale_log2e, tq_h, tq_w);
         }
         if (next >= 0) WIN_PREFETCH(next, 4)
         finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
@@ -603,10 +616,11 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
 #pragma unroll
             for (int b = 0; b < GLB_NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
             const int nb = min(GLB_NB, nblk - c0);
+            // (the full-chunk specialisation costs this kernel registers it does not have: it spills)
             if (key0[GLB_NB - 1] + 32 > S)
-                attn_chunk_step<D, GLB_NB, true, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+                attn_chunk_step<D, GLB_NB, true, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             else
-                attn_chunk_step<D, GLB_NB, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+                attn_chunk_step<D, GLB_NB, false, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             if (c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
         }
     }
