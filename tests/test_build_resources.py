@@ -1,0 +1,46 @@
+"""Host-side checks of the build's register accounting: the GEMM and attention kernels are written to a
+budget of 256 VGPRs (two waves per SIMD); the build records what the compiler reports and refuses spills."""
+import os
+
+import pytest
+
+from paper_2605_17633_amd import build
+
+SAMPLE = """\
+a.hip:43:1: remark: Function Name: _Z3fooPf [-Rpass-analysis=kernel-resource-usage]
+   43 | {
+      | ^
+a.hip:43:1: remark:     TotalSGPRs: 22 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     VGPRs: 250 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     AGPRs: 0 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     ScratchSize [bytes/lane]: 140 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     Occupancy [waves/SIMD]: 2 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     VGPRs Spill: 34 [-Rpass-analysis=kernel-resource-usage]
+a.hip:43:1: remark:     LDS Size [bytes/block]: 0 [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark: Function Name: _Z3barPf [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark:     VGPRs: 12 [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]
+"""
+
+
+def test_resource_remarks_are_parsed():
+    ks = build._resources(SAMPLE)
+    assert [k["name"] for k in ks] == ["_Z3fooPf", "_Z3barPf"]
+    assert ks[0]["VGPRs"] == 250 and ks[0]["VGPRs Spill"] == 34 and ks[0]["ScratchSize"] == 140
+    assert ks[0]["Occupancy"] == 2 and ks[1]["VGPRs Spill"] == 0
+
+
+def test_hot_kernels_keep_their_register_budget():
+    path = os.path.join(build.ROOT, "_build", "kernel_resources.txt")
+    if not os.path.exists(path):
+        pytest.skip("library not built in this tree")
+    hot = []
+    for line in open(path):
+        f = line.split()
+        name, kv = f[1], dict(x.split("=") for x in f[2:])
+        if "gemm_bf16_nt_kernel" in name or "attn_" in name:
+            hot.append((name, {k: int(v) for k, v in kv.items()}))
+    assert len(hot) >= 20, "expected every GEMM and attention instantiation in the record"
+    for name, r in hot:
+        assert r["spill"] == 0 and r["scratch"] == 0, (name, r)
+        assert r["vgprs"] + r["agprs"] <= 256, (name, r)
