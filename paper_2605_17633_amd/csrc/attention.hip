@@ -16,20 +16,27 @@
 // the transposing LDS read of gfx950 (ds_read_b64_tr_b16: a 16-lane group reads
 // 4 rows x 16 columns and every lane receives one column), so V is staged
 // exactly like K and never transposed in memory.
-// Key blocks are processed in chunks of up to four (128 keys): all score MFMAs
-// of the chunk first, one max / one rescale of the running output per chunk,
-// then all P V MFMAs, so that the matrix pipe sees long runs of independent work.
-// Bias: per wave, U = Q R^T is formed once with the MFMA for both tables and
-// scattered into per-query rows B^H[q][key_row], B^W[q][key_col] in LDS
-// (pre-multiplied by log2 e); the inner loop adds two table look-ups per score.
+// Key blocks are processed in chunks of two (64 keys; the register budget of two
+// waves per SIMD): all score MFMAs of the chunk first, one max / one rescale of
+// the running output per chunk, then all P V MFMAs.
+// Bias: per wave, U = Q R^T is formed once with the MFMA for both tables and kept
+// in LDS as fp16, pre-multiplied by log2 e; the inner loop adds two table
+// look-ups per score through per-key byte offsets.  Global kernel: scattered into
+// entry-major rows B^H[key_row][q], B^W[key_col][q]; window kernel: stored as the
+// MFMA tile comes out, U[q][m], a key being entry q_row - key_row + w - 1.
+// Memory requests are spread over a problem's / a tile's phases (see the prefetch
+// macros): a wave whose loads do not fit the CU's request queues waits instead of
+// computing, and a wait placed behind a branch or on a value that is used at once
+// drains every load and store in flight.
 //
 // Two launch shapes:
 //   window kernel: persistent workgroups looping over (window, head) problems, one
 //                  wave per 32-query tile (= mask tile of 32), the window's whole K
-//                  and V in LDS, the next problem's Q/K/V prefetched into registers,
-//                  the rel-pos tables resident in LDS;
-//   global kernel: one workgroup per (128-query mask tile, image, head), 4 waves,
-//                  active 128-key tiles streamed through LDS with register prefetch.
+//                  and V in LDS, the next problem's K, V, Q prefetched into registers
+//                  in three pieces, the rel-pos tables resident in LDS;
+//   global kernel: one workgroup per (128-query mask tile, image, head), 4 waves, two
+//                  workgroups per CU, active 128-key tiles streamed through LDS with
+//                  register prefetch (K and V requested at different points).
 #include "common.h"
 
 namespace {
