@@ -522,7 +522,9 @@ attn_window_kernel(AttnParams P, int n_groups)
 
 // ------------------------------------------------------------------ global kernel
 constexpr int GLB_TILE = 128;
-constexpr int GLB_NB = 2;              // key blocks per softmax chunk (register budget: 2 waves per SIMD)
+// key blocks per softmax chunk: the register budget of two waves per SIMD allows 2 at d = 80 and 4 up to d = 64
+// (the chunk step specialised for full chunks spills in this kernel at either size)
+template <int D> constexpr int glb_nb() { return D <= 64 ? 4 : 2; }
 // Bias rows of the global kernel are held as fp16 (11 significant bits on log2e * q.r, below the bf16
 // rounding of the probabilities that feed the second product): at w = 64 that brings a workgroup to
 // 78 KB of LDS, so two workgroups share a CU and one hides the other's LDS, MFMA and barrier latency.
@@ -572,6 +574,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
     }
     GlbTab *tq = reinterpret_cast<GlbTab *>(Tb + wave * wsb);
 
+    constexpr int NB = glb_nb<D>();
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
     u32x4 rk[LOADS], rv[LOADS];
     int rcell = 0;
@@ -614,21 +617,21 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
         ATTN_STORE_TILE()
         LDS_BARRIER();
         const int kt_next = a + 1 < P.n_pre ? a + 1 : qt;
-        if (a + 1 < nact) ATTN_LOAD_TILE(kt_next, 1)
+        if (a + 1 < nact) ATTN_LOAD_TILE(kt_next, NB < GLB_TILE / 32 ? 1 : 3)     // one step per tile: nothing to put V between
         const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
 #pragma unroll
-        for (int c0 = 0; c0 < GLB_TILE / 32; c0 += GLB_NB) {
+        for (int c0 = 0; c0 < GLB_TILE / 32; c0 += NB) {
             if (c0 >= nblk) break;
-            int blk[GLB_NB], key0[GLB_NB];
+            int blk[NB], key0[NB];
 #pragma unroll
-            for (int b = 0; b < GLB_NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
-            const int nb = min(GLB_NB, nblk - c0);
-            // (the full-chunk specialisation costs this kernel registers it does not have: it spills)
-            if (key0[GLB_NB - 1] + 32 > S)
-                attn_chunk_step<D, GLB_NB, true, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+            for (int b = 0; b < NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
+            const int nb = min(NB, nblk - c0);
+            const bool ragged = key0[NB - 1] + 32 > S;
+            if (ragged)
+                attn_chunk_step<D, NB, true, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             else
-                attn_chunk_step<D, GLB_NB, false, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
-            if (c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
+                attn_chunk_step<D, NB, false, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+            if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
         }
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
