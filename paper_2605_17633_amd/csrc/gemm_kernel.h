@@ -447,9 +447,33 @@ gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const floa
         v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
         v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
     }
+    // destination row and its old value (mapped epilogues) are requested before the partial sums are walked
+    constexpr bool MAPPED = EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER;
+    int idx = 0, mb = 0;
+    if (MAPPED) {
+        mb = m / rm.rows_per_batch;
+        idx = rm.map[(long)mb * rm.map_batch_stride + (m - mb * rm.rows_per_batch)];
+    }
     float acc[8] = { 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f };
     const float *src = partial + ((long)slot * parts * BM + row) * BN + col;
-    for (int p = 0; p < parts; ++p) {
+    // four slots' loads in flight at a time; the additions keep the slot order (the result does not depend on
+    // how the loads are grouped)
+    int p = 0;
+    for (; p + 4 <= parts; p += 4) {
+        float4 y[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(src + (long)(p + u) * BM * BN);
+            y[u][0] = s4[0];
+            y[u][1] = s4[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc[0] += y[u][0].x; acc[1] += y[u][0].y; acc[2] += y[u][0].z; acc[3] += y[u][0].w;
+            acc[4] += y[u][1].x; acc[5] += y[u][1].y; acc[6] += y[u][1].z; acc[7] += y[u][1].w;
+        }
+    }
+    for (; p < parts; ++p) {
         const float4 *s4 = reinterpret_cast<const float4 *>(src + (long)p * BM * BN);
         float4 y0 = s4[0], y1 = s4[1];
         acc[0] += y0.x; acc[1] += y0.y; acc[2] += y0.z; acc[3] += y0.w;
@@ -461,11 +485,9 @@ gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const floa
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
     }
-    if (EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER) {
-        int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
-        int idx = rm.map[(long)b * rm.map_batch_stride + p];
+    if (MAPPED) {
         if (idx < 0 || idx >= rm.dst_rows_per_batch) return;
-        uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)b * rm.dst_rows_per_batch + idx) * ld.c + ncol);
+        uint4 *dst = reinterpret_cast<uint4 *>(C + ((long)mb * rm.dst_rows_per_batch + idx) * ld.c + ncol);
         if (EPI == SSAM_EPI_BIAS_SCATTER_ADD) {
             float o[8];
             unpack_bf16x8(*dst, o);

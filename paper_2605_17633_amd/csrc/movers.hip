@@ -75,13 +75,26 @@ ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, i
         return;
     }
     const uint4 *xrow = x + ((long)b * Nin + src) * chunks;
+    // every load of the row is requested before the first is used, without predicates (a chunk index past the
+    // row re-reads its last chunk and is masked in the arithmetic): behind `c < chunks` each load would be
+    // waited for on its own, one memory round trip after the other
+    uint4 raw[MAXC];
+    float4 g0[MAXC], g1[MAXC], b0[MAXC], b1[MAXC];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) raw[i] = xrow[min(lane + 64 * i, chunks - 1)];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = min(lane + 64 * i, chunks - 1);
+        const float4 *g4 = reinterpret_cast<const float4 *>(gamma) + 2 * c;
+        const float4 *b4 = reinterpret_cast<const float4 *>(beta) + 2 * c;
+        g0[i] = g4[0]; g1[i] = g4[1]; b0[i] = b4[0]; b1[i] = b4[1];
+    }
     float v[MAXC][8];
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
-        int c = lane + 64 * i;
-        if (c < chunks) {
-            unpack_bf16x8(xrow[c], v[i]);
+        unpack_bf16x8(raw[i], v[i]);
+        if (lane + 64 * i < chunks) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += v[i][e];
         }
@@ -91,8 +104,7 @@ ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, i
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
-        int c = lane + 64 * i;
-        if (c < chunks) {
+        if (lane + 64 * i < chunks) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) { float t = v[i][e] - mean; q += t * t; }
         }
@@ -102,11 +114,8 @@ ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, i
     for (int i = 0; i < MAXC; ++i) {
         int c = lane + 64 * i;
         if (c < chunks) {
-            const float4 *g4 = reinterpret_cast<const float4 *>(gamma) + 2 * c;
-            const float4 *b4 = reinterpret_cast<const float4 *>(beta) + 2 * c;
-            float4 g0 = g4[0], g1 = g4[1], b0 = b4[0], b1 = b4[1];
-            float gg[8] = { g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w };
-            float bb[8] = { b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w };
+            float gg[8] = { g0[i].x, g0[i].y, g0[i].z, g0[i].w, g1[i].x, g1[i].y, g1[i].z, g1[i].w };
+            float bb[8] = { b0[i].x, b0[i].y, b0[i].z, b0[i].w, b1[i].x, b1[i].y, b1[i].z, b1[i].w };
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * inv * gg[e] + bb[e];
