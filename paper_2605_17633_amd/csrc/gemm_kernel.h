@@ -239,17 +239,13 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
             GEMM_LOAD_W(kt + 1, 3)
             GEMM_SGB(0x100, MT);
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
-            GEMM_SGB(0x020, NT);
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); }
-            GEMM_SGB(0x020, NT);
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); }
-            GEMM_SGB(0x020, NT);
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); }
-            GEMM_SGB(0x020, NT);
+            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
             LDS_BARRIER();
         }
         GEMM_LOAD_AFRAGS(buf, 0, 0)
