@@ -440,12 +440,20 @@ def main():
         B.ssam_encoder_forward(x, structs, flags, cl, cg, wtab, wsig, gtab, gtab, scores, kp, ws_buf,
                                qkv_events=events, plan=plan)
 
+    # A recorded event costs the stream about 6 us (measured: 64 of them took 1.1 % off the step), so the qkv
+    # contraction is timed in every fourth windowed block and in one global block, not in all 32.
+    win_blocks = [i for i in range(shape.depth) if i not in shape.global_blocks]
+    timed_win = win_blocks[1::4]
+    timed_glob = list(shape.global_blocks)[:1]
+    timed_blocks = set(timed_win + timed_glob)
+
     def timed(cl, cg, kp, steps, warmup, with_events):
         for _ in range(warmup):
             step(cl, cg, kp)
         evs = None
-        if with_events:
-            evs = [(C.c_void_p * (2 * shape.depth))(*[hip.event() for _ in range(2 * shape.depth)]) for _ in range(steps)]
+        if with_events:      # events only around the sampled blocks' contractions (NULL entries are skipped)
+            evs = [(C.c_void_p * (2 * shape.depth))(*[hip.event() if i // 2 in timed_blocks else None
+                                                     for i in range(2 * shape.depth)]) for _ in range(steps)]
         marks = [hip.event() for _ in range(steps + 1)]
         stream = torch.cuda.current_stream().cuda_stream
         torch.cuda.synchronize()
@@ -473,9 +481,11 @@ def main():
 
     # ---- roofline of the dominant kernel: the qkv contraction, from the events recorded in the timed region
     flops_step, qkv_flops = encoder_flops(shape, g, Bn, r, rho, K)
-    qkv_ms = [[hip.elapsed_ms(e[2 * i], e[2 * i + 1]) for i in range(shape.depth)] for e in evs]
-    qkv_ms = np.array(qkv_ms)                                            # [steps, depth]
-    avg_ms = float(qkv_ms.mean())
+    t_win = np.array([[hip.elapsed_ms(e[2 * i], e[2 * i + 1]) for i in timed_win] for e in evs])      # [steps, sampled]
+    t_glob = np.array([[hip.elapsed_ms(e[2 * i], e[2 * i + 1]) for i in timed_glob] for e in evs])
+    n_win, n_glob = len(win_blocks), len(shape.global_blocks)
+    # average launch duration over the step's launches: windowed and global blocks weighted by their counts
+    avg_ms = float((n_win * t_win.mean() + n_glob * (t_glob.mean() if t_glob.size else 0.0)) / (n_win + n_glob))
     avg_flops = float(np.mean(qkv_flops))
     achieved = avg_flops / (avg_ms * 1e-3) / 1e12
     rows_local = (-(-g // shape.ws)) ** 2 * shape.ws ** 2
@@ -484,10 +494,14 @@ def main():
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": profile_traffic(shape.name),
         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": shape.depth,
+        "launches_timed_per_step": len(timed_blocks),
+        "timed_blocks": {"windowed": timed_win, "global": timed_glob,
+                         "avg_ms_windowed": round(float(t_win.mean()), 4),
+                         "avg_ms_global": round(float(t_glob.mean()), 4) if t_glob.size else None},
         "flops_per_launch": avg_flops,
         "shape": f"M={Bn * n} (real tokens; the {Bn * (rows_local - n)} padding slots of the windows are filled with the bias), "
                  f"N={3 * shape.D}, K={shape.D}",
-        "qkv_share_of_step": round(float(qkv_ms.sum(axis=1).mean()) / ms_per_step, 4),
+        "qkv_share_of_step": round(avg_ms * shape.depth / ms_per_step, 4),
     }
 
     out = {

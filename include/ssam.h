@@ -294,9 +294,10 @@ int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cf
  * computed once, in the first layer) before the first block reads them.
  * workspace >= ssam_encoder_workspace_bytes(cfg_local, cfg_global).
  * qkv_events: optional instrumentation, host array of 2*n_blocks hipEvent_t
- * (NULL = none): events [2i] and [2i+1] are recorded on the stream right before
- * and right after block i's qkv contraction, so that a benchmark can time that
- * kernel inside its own timed region. */
+ * (NULL = none; a NULL entry = that block is not timed): events [2i] and [2i+1]
+ * are recorded on the stream right before and right after block i's qkv
+ * contraction, so that a benchmark can time that kernel inside its own timed
+ * region.  A recorded event costs the stream a few microseconds. */
 size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global);
 int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
                          const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global,

@@ -156,10 +156,10 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     if (!padded) {
         rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
         if (rc != SSAM_OK) return rc;
-        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+        if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
         rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
         if (rc != SSAM_OK) return rc;
-        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
+        if (qkv_events && qkv_events[1] && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
         rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, nullptr,
                                    B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
                                    1.0f / sqrtf((float)g.d), stream);
@@ -180,13 +180,13 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
         }
         rc = ssam_ln_gather(x, pt.real_spatial, g.N, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.N, D, stream);
         if (rc != SSAM_OK) return rc;
-        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+        if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
         GemmRowMap to_slot = { pt.real_slot, g.N, g.N, g.Nout };
         rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS_SCATTER, to_slot, 0, split, GEMM_SPLIT_WS_BYTES, st);
         if (rc != SSAM_OK) return rc;
         rc = ssam_fill_bias_rows(qkv, 3L * D, w->bqkv, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
         if (rc != SSAM_OK) return rc;
-        if (qkv_events && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
+        if (qkv_events && qkv_events[1] && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
         rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, pt.slot_row,
                                    B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
                                    1.0f / sqrtf((float)g.d), stream);
