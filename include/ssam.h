@@ -139,8 +139,8 @@ int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M,
                 int dst_rows_per_batch, void *stream);
 
 /* The same with the workgroup tile forced (tuning and tests): tile = 0 picks
- * automatically, 1 = 256x256 with 8 waves (needs N % 256 == 0), 2 = 256x128,
- * 3 = 128x128.
+ * automatically, 1 = 256x256 with 8 waves (needs N % 256 == 0), 2 = 256x128
+ * (row-major weights only), 3 = 128x128, 4 = 128x256 with 4 waves.
  * With any tile, when the tiles fill at least one round of workgroups and the
  * left-over is under half a round, the left-over tiles run as a second launch
  * of half- or quarter-size tiles; results do not depend on the tile choice
@@ -171,8 +171,10 @@ int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed,
  * i.e. the 1 KB operand-B fragment of every (32 output channels, 16 input
  * channels) cell is contiguous.  ssam_linear_ld with w_packed != 0 (then ldw is
  * ignored) loads such fragments straight into registers and stages only A in
- * LDS, which halves its LDS traffic; results are bit-identical to the row-major
- * form.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 32 ==
+ * LDS, which halves its LDS traffic; with the same tile (forced) the results are
+ * bit-identical to the row-major form; the automatic choice may take another
+ * tile for packed weights (the 128x256 one), and then the few left-over tiles
+ * whose K range is cut can differ in fp32 summation order.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 32 ==
  * 0 and K % 16 == 0 (else SSAM_EUNSUPPORTED; ssam_linear_ld takes packed
  * weights only for N % 128 == 0 and K % 64 == 0); W and Wp must not overlap.  Tile
  * 2 (256x128) has no packed form (SSAM_EUNSUPPORTED when forced). */

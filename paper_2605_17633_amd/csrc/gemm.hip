@@ -95,6 +95,7 @@ int launch_tile_packed(int tile, const bf16 *A, const bf16 *W, const float *bias
     switch (tile) {
     case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4, true>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI, 2, 2, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
+    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
     default: return SSAM_EUNSUPPORTED;
     }
 }
@@ -107,30 +108,35 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
     case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
     case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
+    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);   // same plan as packed
     default: return SSAM_EINVAL;
     }
 }
 
 // Pick the tile by a time model in microseconds, fitted on MI355X to the ViT-H layer shapes: a round of
-// workgroups costs nk * t_slab + t_epi (the 256x256 tile, eight waves, moves least data per flop but runs
-// one workgroup per CU, so its epilogue is not hidden; the 128x128 tile runs two per CU, which hides one
-// workgroup's epilogue behind the other's main loop); the
-// left-over launch costs a lone workgroup's walk over its K range, latency bound, plus the reduce.
-int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws)
+// workgroups costs nk * t_slab + t_epi.  The 256x256 tile (eight waves, one workgroup per CU) and the 128x256
+// tile (four waves in a row, two workgroups per CU) give a wave the same 128x64 piece and move the same data
+// per flop; with two independent workgroups per CU one's epilogue overlaps the other's main loop, which is worth
+// 5 us a round behind the GELU epilogue and 1-2.5 us behind the others.  The 128x128 tile (two per CU) moves
+// more data per flop and is for small problems.  The left-over launch costs a lone workgroup's walk over its
+// K range, latency bound, plus the reduce.
+int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws, bool packed)
 {
     struct Cand { int id, bm, bn, tm, tn, slots; double t_slab, t_epi[4]; };   // t_epi: bias, +GELU, scatter-add, scatter
-    const Cand cands[3] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
+    const Cand cands[4] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
                             { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5, 4.5 } },
-                            { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8, 4.0 } } };
+                            { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8, 4.0 } },
+                            { 4, 128, 256, 128, 128, 512, 1.71, { 5.5, 9.0, 11.5, 5.5 } } };
     const int nk = ssam_div_up(K, GEMM_BK);
     int best = 3;
     double best_time = 1e30;
     for (const Cand &c : cands) {
         if (c.id == 2) continue;    // 256x128 is never the fastest on these shapes: kept as a forced choice only
+        if (c.id == 4 && !packed) continue;   // with W in LDS a 128x256 workgroup needs 96 KB: one per CU, nothing overlaps
         const int subs = (c.bm / c.tm) * (c.bn / c.tn);
         const int total = ssam_div_up(M, c.bm) * ssam_div_up(N, c.bn);
         const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
-        const double round = nk * c.t_slab + c.t_epi[epilogue];   // packed weights speed both tiles up alike: same choice, same sums
+        const double round = nk * c.t_slab + c.t_epi[epilogue];
         double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
         if (plan.rem != 0) {
             const int n_sub = plan.rem * subs;
@@ -150,7 +156,7 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
     const SplitWs ws = { split_ws, split_ws_bytes };
     const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
     bf16 *c = (bf16 *)C;
-    if (tile == 0) tile = pick_tile(M, N, K, epilogue, ws);
+    if (tile == 0) tile = pick_tile(M, N, K, epilogue, ws, packed);
     if (packed) {
         switch (epilogue) {
         case SSAM_EPI_BIAS: return launch_tile_packed<SSAM_EPI_BIAS>(tile, a, w, bias, c, M, N, K, ld, rm, ws, st);
@@ -207,7 +213,7 @@ extern "C" int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, in
     if (w_packed && (N % 128 != 0 || K % GEMM_BK != 0)) return SSAM_EUNSUPPORTED;
     if (lda < K || ldc < N || lda % 8 || ldc % 8 || (!w_packed && (ldw < K || ldw % 8))) return SSAM_EINVAL;
     if (workspace && !ssam_aligned16(workspace)) return SSAM_EINVAL;
-    if (tile < 0 || tile > 3) return SSAM_EINVAL;
+    if (tile < 0 || tile > 4) return SSAM_EINVAL;
     if (w_packed && tile == 2) return SSAM_EUNSUPPORTED;
     GemmRowMap rm = { nullptr, 1, 0, 1 };
     if (epilogue == SSAM_EPI_BIAS_SCATTER_ADD || epilogue == SSAM_EPI_BIAS_SCATTER) {

@@ -85,7 +85,7 @@ __device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t,
 }
 
 template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
-__global__ void __launch_bounds__(64 * WGM * WGN)
+__global__ void __launch_bounds__(64 * WGM * WGN, (BN == 256 && WGM * WGN == 4 && WPACK) ? 2 : 1)
 gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                     bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
 {

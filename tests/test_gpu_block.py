@@ -237,13 +237,14 @@ def test_encoder_forward_small_stack():
     torch.cuda.synchronize()
     got = to_np(xd).reshape(x.shape)
     keep_gpu = keep.cpu().numpy()
-    # the same stack with the Linear weights in MFMA fragment order: bit-identical
+    # the same stack with the Linear weights in MFMA fragment order: the same products; bit-identical where the
+    # tile plans agree, else equal up to the summation order of the left-over tiles whose K range is cut
     packed = [B.pack_block_weights(w) for w in wds]
     xp = dev_bf16(x.reshape(B_, n, shape.D))
     B.ssam_encoder_forward(xp, [B.block_weights_struct(w) for w in packed], flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab,
                            scores, keep, ws_buf)
     torch.cuda.synchronize()
-    assert torch.equal(xp, xd)
+    assert_close(to_np(xp), to_np(xd).astype(np.float64), "packed against row-major weights", tol=1e-2)
     for b in range(B_):
         ref, keep_ref = oracle.encoder(x[b], [oracle.BlockWeights(**w) for w in wts], shape.heads, shape.ws,
                                        shape.global_blocks, 4, r, rho)

@@ -128,7 +128,7 @@ def _gemm_ref(A, W, b):
     return A.astype(np.float64) @ W.astype(np.float64).T + b.astype(np.float64)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("M,N,K", [(300, 256, 64), (1000, 512, 192), (513, 768, 768), (64, 256, 128)])
 def test_linear_bias_and_gelu(tile, M, N, K):
     announce("linear", tile, M, N, K)
@@ -201,7 +201,8 @@ def test_linear_tail_cut_along_k(tile, M, N, epi):
 
 
 @pytest.mark.parametrize("tile,M,N,K,epi", [(1, 700, 512, 192, 0), (3, 333, 384, 64, 1), (0, 8400, 2048, 2048, 0),
-                                            (1, 8400, 2048, 128, 2), (3, 4200, 2048, 2048, 0)])
+                                            (1, 8400, 2048, 128, 2), (3, 4200, 2048, 2048, 0),
+                                            (4, 8400, 2048, 2048, 2), (4, 700, 512, 192, 1)])
 def test_linear_packed_weights(tile, M, N, K, epi):
     """Weights in MFMA fragment order (ssam_pack_weight): same bits as the row-major form, on the plain,
     left-over and K-split launches and with every epilogue."""
@@ -226,7 +227,10 @@ def test_linear_packed_weights(tile, M, N, K, epi):
         o1 = o2 = None
     o1 = B.ssam_linear_ld(Ad, Wd, bd, o1, epilogue=epi, tile=tile, workspace=ws, **kw)
     o2 = B.ssam_linear_ld(Ad, Wp, bd, o2, epilogue=epi, tile=tile, workspace=ws, w_packed=True, **kw)
-    assert torch.equal(o1, o2)
+    if tile != 0:
+        assert torch.equal(o1, o2)             # the same (forced) tile: the same bits
+    else:                                      # the automatic choice may differ between the layouts
+        assert_close(to_np(o2), to_np(o1).astype(np.float64), "packed against row-major, automatic tile", tol=1e-2)
     if epi == 0:
         assert_close(to_np(o2), _gemm_ref(A, W, b), "packed linear", tol=1e-2)
     with pytest.raises(B.SsamError) as e:
@@ -234,7 +238,8 @@ def test_linear_packed_weights(tile, M, N, K, epi):
     assert e.value.code == B.EUNSUPPORTED
 
 
-@pytest.mark.parametrize("tile,M,N,K,packed", [(0, 500, 256, 128, False), (1, 8400, 2048, 2048, True), (3, 4200, 2048, 128, False)])
+@pytest.mark.parametrize("tile,M,N,K,packed", [(0, 500, 256, 128, False), (1, 8400, 2048, 2048, True), (3, 4200, 2048, 128, False),
+                                                (4, 8400, 2048, 2048, True)])
 def test_linear_mapped_store(tile, M, N, K, packed):
     """SSAM_EPI_BIAS_SCATTER: row m of the product is stored at the mapped row (negative: dropped), the rows
     the map does not name keep their bits; plain, left-over and K-split launches."""
@@ -280,7 +285,8 @@ def _sweep_case(M, N, K):
 @pytest.mark.parametrize("packed", [False, True])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 @pytest.mark.parametrize("tile,M,N,K", [(1, 8400, 2048, 256), (1, 8400, 2048, 1024), (2, 8400, 1024, 256), (2, 8400, 1024, 1024),
-                                        (3, 4200, 2048, 256), (3, 4200, 2048, 1024), (3, 4150, 2048, 1024)])
+                                        (3, 4200, 2048, 256), (3, 4200, 2048, 1024), (3, 4150, 2048, 1024),
+                                        (4, 8400, 2048, 256), (4, 8400, 2048, 1024), (4, 8350, 2048, 1024)])
 def test_linear_every_instantiation(tile, M, N, K, epi, packed):
     """Every kernel instantiation the dispatcher can reach: large tile, its left-over launch (plain at K = 256,
     cut along K at K = 1024 with a workspace), each epilogue, row-major and packed weights, ragged last rows."""
@@ -310,7 +316,8 @@ def test_linear_every_instantiation(tile, M, N, K, epi, packed):
 
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 @pytest.mark.parametrize("tile,M,N,K", [(0, 500, 144, 576), (0, 1000, 576, 144), (3, 333, 288, 1152), (1, 700, 1160, 200),
-                                        (0, 70000, 144, 576), (1, 8400, 2056, 1096), (3, 4200, 2056, 1096)])
+                                        (0, 70000, 144, 576), (1, 8400, 2056, 1096), (3, 4200, 2056, 1096),
+                                        (4, 8400, 2056, 1096)])
 def test_linear_ragged_widths(tile, M, N, K, epi):
     """N and K that are multiples of 8 only (the stage widths of hierarchical encoders: 144, 288, 576):
     ragged last tile column and ragged last K slab, every epilogue, single, left-over and K-split launches."""
@@ -359,7 +366,7 @@ def test_linear_row_strides():
     assert e.value.code == B.EINVAL
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_linear_scatter_add(tile):
     announce("linear scatter", tile)
     rng = np.random.default_rng(6)
