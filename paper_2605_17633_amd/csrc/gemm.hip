@@ -7,7 +7,7 @@ struct SplitWs { void *ptr; size_t bytes; };
 
 // How a launch of `total` large tiles over `slots` concurrent workgroups is cut: `rem` left-over large
 // tiles go to a second launch of `subs` smaller tiles each (0: none, when the tiles do not fill one
-// round, fill the last one exactly, or fill more than half of it), and that launch also cuts K into
+// round, fill the last one exactly, fill more than half of it, or give every CU a workgroup), and that launch also cuts K into
 // `parts` ranges (1: no) when a workspace is there, K is long and the left-over is small.  A problem of less
 // than one round is treated as all left-over when cutting K gives it at least twice the workgroups.
 struct TailPlan { int rem, parts; };
@@ -29,7 +29,10 @@ TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes
         }
         p.rem = 0;
     }
-    if (p.rem > slots / 2) p.rem = 0;
+    // A last round that is more than half full stays in the main launch.  So does one that gives every CU a
+    // workgroup (tiles that run two per CU: a lone workgroup has the CU to itself and finishes in about 0.6 of
+    // a full round's time, sooner than the same work as a second launch of smaller tiles).
+    if (p.rem > slots / 2 || p.rem >= 256) p.rem = 0;
     if (p.rem == 0) return p;
     const int n_sub = p.rem * subs;
     int parts = nk / 4;                         // at least 4 slabs per workgroup
@@ -137,7 +140,9 @@ int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws, bool packed)
         const int total = ssam_div_up(M, c.bm) * ssam_div_up(N, c.bn);
         const TailPlan plan = plan_tail(total, c.slots, nk, subs, (size_t)c.tm * c.tn * sizeof(float), ws);
         const double round = nk * c.t_slab + c.t_epi[epilogue];
-        double t = (double)ssam_div_up(total - plan.rem, c.slots) * round;
+        const int in_main = total - plan.rem, last = in_main % c.slots;
+        double t = (double)(in_main / c.slots) * round;
+        if (last != 0) t += round * (c.slots > 256 && last * 2 <= c.slots ? 0.62 : 1.0);   // lone workgroups on their CUs
         if (plan.rem != 0) {
             const int n_sub = plan.rem * subs;
             t += plan.parts > 1 ? ssam_div_up(nk, plan.parts) * 0.9 + 11.0 : (nk * 0.75 + 5.0) * (1.0 + n_sub / 1024.0);
