@@ -129,7 +129,7 @@ int pick_tile(int M, int N, int K, int epilogue, const SplitWs &ws, bool packed)
     const Cand cands[4] = { { 1, 256, 256, 128, 128, 256, 1.73, { 5.1, 13.6, 13.5, 6.0 } },
                             { 2, 256, 128, 128, 128, 256, 1.15, { 4.0, 9.0, 9.5, 4.5 } },
                             { 3, 128, 128, 64, 128, 512, 1.10, { 3.5, 6.6, 6.8, 4.0 } },
-                            { 4, 128, 256, 128, 128, 512, 1.71, { 5.5, 9.0, 11.5, 5.5 } } };
+                            { 4, 128, 256, 128, 128, 512, 1.71, { 5.0, 9.0, 11.5, 5.5 } } };
     const int nk = ssam_div_up(K, GEMM_BK);
     int best = 3;
     double best_time = 1e30;
