@@ -73,6 +73,32 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
     const TailPlan plan = plan_tail(total, slots, nk, SUB_M * SUB_N, (size_t)TM * TN * sizeof(float), ws);
     const int rem = plan.rem, parts = plan.parts;
     tr.tile_count = total - rem;
+    if constexpr (WGM * WGN == 4 && WPACK) if (rem != 0 && tr.tile_count != 0) {
+        // four-wave large tiles: whole rounds and left-over share one launch (see the fused kernel); a K-split
+        // left-over is then finished by the reduce kernel as usual
+        GemmTileRange tt = tr;
+        tt.tile_begin = total - rem;
+        tt.tile_count = rem;
+        const int n_sub = rem * SUB_M * SUB_N;
+        const int n_tail = ssam_div_up(n_sub * parts, 8) * 8, n_main = ssam_div_up(tr.tile_count, 8) * 8;
+        constexpr size_t lds_main = gemm_lds_bytes<BM, BN, WGM, WGN, WPACK>(), lds_tail = gemm_lds_bytes<TM, TN, 2, 2, WPACK>();
+        constexpr size_t lds = lds_main > lds_tail ? lds_main : lds_tail;
+        static_assert(lds <= 64 * 1024, "the fused launch stays within the default LDS limit");
+        if (parts > 1) {
+            const GemmSplit sp = { (float *)ws.ptr, parts };
+            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, WPACK>),
+                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, sp, n_tail);
+            SSAM_CHECK_LAUNCH();
+            constexpr int RPB = 256 / (TN / 8);
+            hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
+                               (const float *)ws.ptr, parts, bias, C, M, N, ld, tt, rm);
+        } else {
+            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, EPI, SUB_M, SUB_N, WPACK>),
+                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, whole, n_tail);
+        }
+        SSAM_CHECK_LAUNCH();
+        return SSAM_OK;
+    }
     int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
     if (rc != SSAM_OK || rem == 0) return rc;
     tr.tile_begin = total - rem;

@@ -84,10 +84,13 @@ __device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t,
     n0 = (tn * sub_n + sub % sub_n) * bn;
 }
 
+// The workgroup's work, as a function of its index `bid` in the launch (the kernels below pass blockIdx.x, or
+// blockIdx.x less the workgroups of another kind that share the launch).
 template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
-__global__ void __launch_bounds__(64 * WGM * WGN, (BN == 256 && WGM * WGN == 4 && WPACK) ? 2 : 1)
-gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
-                    bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
+__device__ __forceinline__ void
+gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
+                  bf16 *C, int M, int N, int K, const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm,
+                  const GemmSplit &sp, int bid)
 {
     constexpr int THREADS = 64 * WGM * WGN, RSTEP = THREADS / 8;   // waves in a WGM x WGN grid; rows staged per pass
     constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
@@ -104,7 +107,7 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
     const int parts = EPI == GEMM_EPI_PARTIAL ? sp.parts : 1;
     const int total = tr.tile_count * SUBS * parts;
     const int per_xcd = (total + 7) / 8;
-    const int tl = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int tl = (bid & 7) * per_xcd + (bid >> 3);
     if (tl >= total) return;
     const int kpart = tl % parts, slot = tl / parts;            // slot: sub-tile index within this launch
     int m0, n0;
@@ -417,6 +420,34 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
 #pragma unroll
             for (int pass = 0; pass < PASSES; ++pass) { old[pass] = old_next[pass]; drow[pass] = drow_next[pass]; }
         }
+    }
+}
+
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
+__global__ void __launch_bounds__(64 * WGM * WGN, (BN == 256 && WGM * WGN == 4 && WPACK) ? 2 : 1)
+gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
+                    bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
+{
+    gemm_bf16_nt_body<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, sp, (int)blockIdx.x);
+}
+
+// Whole rounds and left-over tiles in ONE launch (both kinds of workgroup have 256 threads): the first `n_tail`
+// workgroups (a multiple of 8, so that the XCD of a workgroup index stays the same for both kinds) run the
+// left-over sub-tiles (TEPI = the epilogue proper, or GEMM_EPI_PARTIAL with K ranges), the others the large
+// tiles.  The left-over workgroups are dispatched first and finish while the first round of large tiles runs,
+// instead of running as a launch of their own on a mostly idle chip.
+template <int BM, int BN, int EPI, int WGM, int WGN, int TM, int TN, int TEPI, int SUB_M, int SUB_N, bool WPACK>
+__global__ void __launch_bounds__(256, 2)
+gemm_bf16_nt_fused_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
+                          bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr_main, GemmTileRange tr_tail,
+                          GemmRowMap rm, GemmSplit sp_tail, int n_tail)
+{
+    static_assert(WGM * WGN == 4, "both kinds of workgroup are four waves");
+    if ((int)blockIdx.x < n_tail) {
+        gemm_bf16_nt_body<TM, TN, TEPI, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr_tail, rm, sp_tail, (int)blockIdx.x);
+    } else {
+        const GemmSplit whole = { nullptr, 1 };
+        gemm_bf16_nt_body<BM, BN, EPI, 1, 1, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr_main, rm, whole, (int)blockIdx.x - n_tail);
     }
 }
 
