@@ -217,8 +217,9 @@ def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab,
     del qkv, o
     # routed MLP (LN2 + gather, fc1 + GELU, fc2 + scatter-add), in place on a scratch copy
     xs = x0.clone()
-    ms = run(lambda: B.ssam_routed_mlp(xs, keep, w0["ln2_g"], w0["ln2_b"], 1e-6, w0["w1"], w0["b1"], w0["w2"], w0["b2"],
-                                       workspace=ws_buf))
+    w1p, w2p = B.ssam_pack_weight(w0["w1"]), B.ssam_pack_weight(w0["w2"])      # the form the encoder uses
+    ms = run(lambda: B.ssam_routed_mlp_packed(xs, keep, w0["ln2_g"], w0["ln2_b"], 1e-6, w1p, w0["b1"], w2p, w0["b2"],
+                                              workspace=ws_buf))
     parts["routed_mlp"] = mfma(ms, 4.0 * Bn * K * D * Dm)
     # scores (one read of x) and keep-set selection (latency bound: microseconds, once per image for all blocks)
     ms = run(lambda: B.ssam_score_tokens(x0.view(Bn, g, g, D), scores=scores, workspace=ws_buf))
@@ -265,6 +266,7 @@ def sweep_leg(torch, hip, B, inputs, seed, reps=5):
         return hip.elapsed_ms(e0, e1) / reps
 
     out = {"batch": Bn}
+    w1p, w2p = B.ssam_pack_weight(w["w1"]), B.ssam_pack_weight(w["w2"])
     for r in (0.2, 0.3, 0.4, 0.6, 1.0):
         T = n // 128
         n_pre = min(T, int(math.floor(r * T + 1e-6)))
@@ -273,7 +275,7 @@ def sweep_leg(torch, hip, B, inputs, seed, reps=5):
         fl_a = 4.0 * 128 * 128 * d * tiles * h * Bn
         K = B.ssam_keep_count(n, r)
         keep = B.ssam_select_tokens(scores, K)
-        ms_m = run(lambda: B.ssam_routed_mlp(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w["w1"], w["b1"], w["w2"], w["b2"], workspace=ws_buf))
+        ms_m = run(lambda: B.ssam_routed_mlp_packed(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w1p, w["b1"], w2p, w["b2"], workspace=ws_buf))
         fl_m = 4.0 * Bn * K * D * Dm
         out[f"density_{r}"] = {
             "attention_global": {"us": round(ms_a * 1e3, 1), "tflops": round(fl_a / ms_a / 1e9, 1),
@@ -305,10 +307,14 @@ def hiera_leg(torch, hip, B, seed, Bn=4, reps=5):
              "w1": (torch.randn((Dm, D), generator=gen, device=dev) * 0.02).to(bf), "b1": torch.randn(Dm, generator=gen, device=dev) * 0.02,
              "w2": (torch.randn((D, Dm), generator=gen, device=dev) * 0.02).to(bf), "b2": torch.randn(D, generator=gen, device=dev) * 0.02}
         ws_buf = torch.empty(B.ssam_routed_mlp_workspace_bytes(Bn, n, D, Dm), dtype=torch.uint8, device=dev)
+        wp1, wp2 = (B.ssam_pack_weight(w["w1"]), B.ssam_pack_weight(w["w2"])) if D % 128 == 0 else (None, None)
         for r in (1.0, 0.7, 0.5, 0.3):
             K = B.ssam_keep_count(n, r)
             keep = B.ssam_select_tokens(scores, K)
-            fn = lambda: B.ssam_routed_mlp(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w["w1"], w["b1"], w["w2"], w["b2"], workspace=ws_buf)
+            if D % 128 == 0:          # packed weights need widths that are multiples of 128 (only the last stage)
+                fn = lambda: B.ssam_routed_mlp_packed(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, wp1, w["b1"], wp2, w["b2"], workspace=ws_buf)
+            else:
+                fn = lambda: B.ssam_routed_mlp(x, keep, w["ln2_g"], w["ln2_b"], 1e-6, w["w1"], w["b1"], w["w2"], w["b2"], workspace=ws_buf)
             for _ in range(2):
                 fn()
             torch.cuda.synchronize()

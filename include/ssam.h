@@ -235,6 +235,13 @@ int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln_g, const f
                     const void *w1, const float *b1, const void *w2, const float *b2,
                     int B, int N, int D, int Dm, int K,
                     void *workspace, size_t workspace_bytes, void *stream);
+/* The same with w1 and w2 in MFMA fragment order (ssam_pack_weight; D and Dm
+ * multiples of 128, else SSAM_EUNSUPPORTED): the form the encoder block uses
+ * when ssam_block_weights.packed is set. */
+int ssam_routed_mlp_packed(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                           const void *w1p, const float *b1, const void *w2p, const float *b2,
+                           int B, int N, int D, int Dm, int K,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Encoder block and stack                                                   */

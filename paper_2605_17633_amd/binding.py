@@ -262,18 +262,24 @@ def ssam_routed_mlp_workspace_bytes(B, K, D, Dm) -> int:
     return lib().ssam_routed_mlp_workspace_bytes(C.c_int(B), C.c_int(K), C.c_int(D), C.c_int(Dm))
 
 
-def ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, workspace=None):
+def ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, workspace=None, w_packed=False):
+    """w_packed: w1 and w2 are outputs of ssam_pack_weight (ssam_routed_mlp_packed)."""
     B, N, D = x.shape
     Dm = w1.shape[0]
     K = keep_idx.shape[1]
     if workspace is None:
         workspace = torch.empty(ssam_routed_mlp_workspace_bytes(B, K, D, Dm), dtype=torch.uint8, device=x.device)
-    _check("ssam_routed_mlp", lib().ssam_routed_mlp(
+    name = "ssam_routed_mlp_packed" if w_packed else "ssam_routed_mlp"
+    _check(name, getattr(lib(), name)(
         _bf(x, "x"), _i32(keep_idx, "keep_idx"), _f32(ln_g, "ln_g"), _f32(ln_b, "ln_b"), C.c_float(eps),
         _bf(w1, "w1"), _f32(b1, "b1"), _bf(w2, "w2"), _f32(b2, "b2"),
         C.c_int(B), C.c_int(N), C.c_int(D), C.c_int(Dm), C.c_int(K),
         C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
     return x
+
+
+def ssam_routed_mlp_packed(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, workspace=None):
+    return ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, workspace=workspace, w_packed=True)
 
 
 # ------------------------------------------------------------------ block / encoder

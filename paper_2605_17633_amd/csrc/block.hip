@@ -111,6 +111,14 @@ extern "C" int ssam_routed_mlp(void *x, const int32_t *keep_idx, const float *ln
     return routed_mlp_impl(x, keep_idx, ln_g, ln_b, eps, w1, b1, w2, b2, false, B, N, D, Dm, K, workspace, workspace_bytes, stream);
 }
 
+extern "C" int ssam_routed_mlp_packed(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
+                                      const void *w1p, const float *b1, const void *w2p, const float *b2,
+                                      int B, int N, int D, int Dm, int K,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return routed_mlp_impl(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, true, B, N, D, Dm, K, workspace, workspace_bytes, stream);
+}
+
 // everything but the padding tables, which sit behind it (so that no step of either half overwrites them
 // and a stack of blocks can build them once)
 static size_t block_core_bytes(const ssam_block_cfg *cfg, const BlockGeom &g)

@@ -140,6 +140,22 @@ def test_routed_mlp(B_, n, D, Dm, rho):
         # the update itself (y - x) carries the result; x + delta would hide errors behind the residual
         assert_close(got[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"mlp delta b={b}",
                      stored=ref[keep[b]])
+    if D % 128 == 0 and Dm % 128 == 0:
+        # the same call with the two weights in MFMA fragment order (ssam_routed_mlp_packed): same bar, same bypass
+        xp = dev_bf16(x)
+        B.ssam_routed_mlp_packed(xp, dev_i32(keep), wd["ln2_g"], wd["ln2_b"], 1e-6, B.ssam_pack_weight(wd["w1"]), wd["b1"],
+                                 B.ssam_pack_weight(wd["w2"]), wd["b2"])
+        gotp = to_np(xp)
+        for b in range(B_):
+            ref = oracle.routed_mlp(x[b], keep[b], wt["ln2_g"], wt["ln2_b"], wt["w1"], wt["b1"], wt["w2"], wt["b2"])
+            rest = np.setdiff1d(np.arange(n), keep[b])
+            assert np.array_equal(gotp[b][rest].view(np.uint32), x[b][rest].view(np.uint32))
+            assert_close(gotp[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"packed mlp delta b={b}",
+                         stored=ref[keep[b]])
+    else:
+        with pytest.raises(B.SsamError) as e:
+            B.ssam_routed_mlp_packed(dev_bf16(x), dev_i32(keep), wd["ln2_g"], wd["ln2_b"], 1e-6, wd["w1"], wd["b1"], wd["w2"], wd["b2"])
+        assert e.value.code == B.EUNSUPPORTED
 
 
 # ------------------------------------------------------------------ encoder block
