@@ -376,7 +376,10 @@ def test_encoder_stack_content_order(depth, g):
             glob = i in shape.global_blocks
             y = oracle.encoder_block(y, oracle.BlockWeights(**w), shape.heads, 0 if glob else shape.ws, 4,
                                      128 if glob else 32, r, keep_gpu[b], order_scores=sc_gpu[b].reshape(g, g))
-        assert_close(got[b] - x[b], y - x[b], f"content-order stack b={b}", stored=y, updates=2 * depth)
+        # a stack of `depth` blocks on stress weights (attention weights x4): every block is held to 2e-2 on its own
+        # update by the single-block cases; over the stack the blocks' errors add as independent contributions
+        assert_close(got[b] - x[b], y - x[b], f"content-order stack b={b}", tol=2e-2 * np.sqrt(depth), stored=y,
+                     updates=2 * depth)
         # and the content-aware result differs from the position-only one (the option is live)
         z = x[b]
         for i, w in enumerate(wts):
