@@ -186,12 +186,17 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         // (the fragments of k-step s of the next slab are requested as soon as this slab's step s has issued),
         // and only A goes through LDS.
         const int ksteps = K / 16;
-        const bf16 *wp = W + ((long)((n0 + wn) >> 5) * ksteps) * 512 + lane * 8;
+        // one pointer per 32-column block of the wave; a block past N (a tile wider than what is left of a
+        // width that is a multiple of 128 only) re-reads the last block of W: its results are never stored
+        const bf16 *wp[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            wp[j] = W + ((long)min(((n0 + wn) >> 5) + j, (N >> 5) - 1) * ksteps) * 512 + lane * 8;
         bf16x8 wf[4][NT];
 #define GEMM_LOAD_W(kt_, ks_)                                                                         \
         {                                                                                             \
             _Pragma("unroll") for (int j = 0; j < NT; ++j)                                            \
-                wf[ks_][j] = *reinterpret_cast<const bf16x8 *>(wp + ((long)j * ksteps + (kt_) * 4 + (ks_)) * 512); \
+                wf[ks_][j] = *reinterpret_cast<const bf16x8 *>(wp[j] + ((long)(kt_) * 4 + (ks_)) * 512); \
         }
 #define GEMM_LOAD_GLOBAL_A(kt_)                                                                       \
         {                                                                                             \

@@ -202,7 +202,10 @@ def test_linear_tail_cut_along_k(tile, M, N, epi):
 
 @pytest.mark.parametrize("tile,M,N,K,epi", [(1, 700, 512, 192, 0), (3, 333, 384, 64, 1), (0, 8400, 2048, 2048, 0),
                                             (1, 8400, 2048, 128, 2), (3, 4200, 2048, 2048, 0),
-                                            (4, 8400, 2048, 2048, 2), (4, 700, 512, 192, 1)])
+                                            (4, 8400, 2048, 2048, 2), (4, 700, 512, 192, 1),
+                                            # widths that are multiples of 128 but not of the 256-wide tiles: the last
+                                            # tile column has no W blocks past N to read
+                                            (4, 700, 384, 192, 0), (1, 309, 1408, 1216, 0), (0, 5102, 1152, 704, 1)])
 def test_linear_packed_weights(tile, M, N, K, epi):
     """Weights in MFMA fragment order (ssam_pack_weight): same bits as the row-major form, on the plain,
     left-over and K-split launches and with every epilogue."""
