@@ -139,7 +139,7 @@ int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M,
                 int dst_rows_per_batch, void *stream);
 
 /* The same with the workgroup tile forced (tuning and tests): tile = 0 picks
- * automatically, 1 = 256x256 with 8 waves (needs N % 256 == 0), 2 = 256x128
+ * automatically, 1 = 256x256 with 8 waves, 2 = 256x128
  * (row-major weights only), 3 = 128x128, 4 = 128x256 with 4 waves.
  * With any tile, when the tiles fill at least one round of workgroups and the
  * left-over is under half a round, the left-over tiles run as a second launch
