@@ -142,8 +142,8 @@ int ssam_linear(const void *A, const void *W, const float *bias, void *C, int M,
  * automatically, 1 = 256x256 with 8 waves, 2 = 256x128
  * (row-major weights only), 3 = 128x128, 4 = 128x256 with 4 waves.
  * With any tile, when the tiles fill at least one round of workgroups and the
- * left-over is under half a round, the left-over tiles run as a second launch
- * of half- or quarter-size tiles; results do not depend on the tile choice
+ * left-over is under half a round, the left-over tiles run as half- or
+ * quarter-size tiles (in the same launch or in a second one); results do not depend on the tile choice
  * beyond fp32 summation order (which is the same: K is never split). */
 int ssam_linear_tiled(const void *A, const void *W, const float *bias, void *C, int M, int N, int K,
                       int epilogue, const int32_t *row_map, int rows_per_batch, int map_batch_stride,
