@@ -179,7 +179,9 @@ __device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const b
 //   tq_h, tq_w: where this lane's query starts in the row-part and column-part bias tables; a key's two
 //           bias terms are read at tq_h + (low half of krc) and tq_w + (high half of krc), in bytes
 //   FULL:   the chunk has all NB blocks (nb is not looked at: no per-block branches, no dummy scores)
-template <int D, int NB, bool RAGGED, bool FULL, typename TabT>
+//   MIXADD: the column part of the bias is added by one mixed-precision fma (fp16 operand widened inside the
+//           instruction) instead of convert + add; costs registers the global kernel does not have at d = 80
+template <int D, int NB, bool RAGGED, bool FULL, typename TabT, bool MIXADD = false>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb_,
                                                 int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
@@ -213,14 +215,27 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
             const unsigned char *tqw = reinterpret_cast<const unsigned char *>(tq_w);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
+                if (RAGGED && key0[b] + 8 * g >= S) {      // all eight keys of this register group lie past S (wave-uniform)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s[b][4 * g + e] = -INFINITY;
+                    continue;
+                }
                 const u32x4 rc = *reinterpret_cast<const u32x4 *>(krc + blk[b] * 32 + 8 * g + 4 * half);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * g + e;
                     const uint32_t c = rc[e];
                     const float bh = (float)*reinterpret_cast<const TabT *>(tqh + (c & 0xffffu));
-                    const float bw = (float)*reinterpret_cast<const TabT *>(tqw + (c >> 16));
-                    float val = s[b][r] * scale_log2e + bh + bw;
+                    float val;
+                    if constexpr (MIXADD) {
+                        static_assert(sizeof(TabT) == 2, "bias tables are fp16");
+                        const uint32_t bw16 = *reinterpret_cast<const uint16_t *>(tqw + (c >> 16));
+                        val = s[b][r] * scale_log2e + bh;            // the compiler forms this mixed fma by itself
+                        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(val) : "v"(bw16), "v"(val));
+                    } else {
+                        const float bw = (float)*reinterpret_cast<const TabT *>(tqw + (c >> 16));
+                        val = s[b][r] * scale_log2e + bh + bw;
+                    }
                     if (RAGGED) val = (key0[b] + 8 * g + 4 * half + e < S) ? val : -INFINITY;
                     s[b][r] = val;
                     mx = fmaxf(mx, val);
@@ -282,11 +297,11 @@ __device__ __forceinline__ void attn_chunk(WaveState<D> &st, const bf16x8 *qf, c
                                            bool ragged, int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
 {
     if (nb == NB) {
-        if (ragged) attn_chunk_step<D, NB, true, true, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
-        else attn_chunk_step<D, NB, false, true, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        if (ragged) attn_chunk_step<D, NB, true, true, TabT, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        else attn_chunk_step<D, NB, false, true, TabT, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
     } else {
-        if (ragged) attn_chunk_step<D, NB, true, false, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
-        else attn_chunk_step<D, NB, false, false, TabT>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        if (ragged) attn_chunk_step<D, NB, true, false, TabT, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
+        else attn_chunk_step<D, NB, false, false, TabT, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, scale_log2e, tq_h, tq_w);
     }
 }
 
@@ -396,7 +411,8 @@ size_t window_lds_bytes(int nqb, int w)
            (size_t)nqb * window_scratch_bytes<D>() + (size_t)SP * 4;
 }
 
-constexpr int WIN_NB = 2;            // key blocks per softmax chunk in the window kernel (register budget: 2 waves per SIMD)
+constexpr int WIN_NB = 1;            // key blocks per softmax chunk in the window kernel: one (with two the kernel has no
+                                     // registers left for the ragged-block and mixed-add savings, and is no faster)
 constexpr int WIN_MAX_LOADS = 5;     // 16-byte K (and V) chunks per thread: 224 keys * 10 chunks / 448 threads
 
 template <int D>
