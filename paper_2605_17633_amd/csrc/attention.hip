@@ -181,6 +181,7 @@ __device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const b
 //   FULL:   the chunk has all NB blocks (nb is not looked at: no per-block branches, no dummy scores)
 //   MIXADD: the column part of the bias is added by one mixed-precision fma (fp16 operand widened inside the
 //           instruction) instead of convert + add; costs registers the global kernel does not have at d = 80
+constexpr float ATTN_LAG = 8.f;
 template <int D, int NB, bool RAGGED, bool FULL, typename TabT, bool MIXADD = false>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb_,
@@ -207,7 +208,7 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    float mx = st.m;
+    float mx = -INFINITY;                    // the chunk's own maximum
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (b < nb) {
@@ -244,26 +245,34 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
         }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = __builtin_amdgcn_exp2f(st.m - mx);      // first chunk: exp2(-inf) = 0
-    st.m = mx;
+    // st.m is the exponent reference of the running sums, not the running maximum: it moves only when a chunk's
+    // maximum exceeds it by more than 2^ATTN_LAG, so probabilities stay below 2^ATTN_LAG (all of a query's terms
+    // carry the same power of two, which the final division removes) and the rescaling of the 32 x D accumulator
+    // is skipped by the whole wave in most chunks.  First chunk: st.m = -inf, every lane moves, alpha = 0.
+    const bool move = mx > st.m + ATTN_LAG;
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+        const float mnew = move ? mx : st.m;
+        const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
+        st.m = mnew;
+        st.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
+    }
+    const float mref = st.m;
     float psum = 0.f;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (b < nb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                s[b][r] = __builtin_amdgcn_exp2f(s[b][r] - mx);
+                s[b][r] = __builtin_amdgcn_exp2f(s[b][r] - mref);
                 psum += s[b][r];
             }
         }
     }
-    st.l = st.l * alpha + psum;
-    {
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
-    }
+    st.l += psum;
     // transposing read: lane li of a 16-lane group points at row (li >> 2), column chunk (li & 3) of a
     // 4-key x 16-feature block and receives the 4 keys of feature column li
     const int li = lane & 15, fblk = (lane >> 4) & 1;
