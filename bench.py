@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="skip the density 1.0 and 0.3 legs")
     ap.add_argument("--no-parts", action="store_true", help="skip the per-entry-point timings")
+    ap.add_argument("--no-fold-ln1", action="store_true",
+                    help="keep LN1 a pass of its own (by default it is folded into the qkv contraction)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain row copy of known size (identity ssam_permute over the input batch), "
@@ -341,7 +343,7 @@ def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
     shape = inputs.SHAPES[name]
     g = 64
     n = g * g
-    wts = [B.pack_block_weights(w) for w in device_weights(torch, seed, shape, g, dev)]
+    wts = [B.pack_block_weights(w, fold_ln1=True) for w in device_weights(torch, seed, shape, g, dev)]
     structs = [B.block_weights_struct(w) for w in wts]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)
@@ -420,7 +422,7 @@ def main():
     x0 = torch.from_numpy(x_host.reshape(Bn, n, shape.D)).to(dev).to(torch.bfloat16).contiguous()
     wts = device_weights(torch, args.seed + 1, shape, g, dev)
     # the four Linear weights of every block go into MFMA fragment order once, at load time (ssam_pack_weight)
-    wts_packed = [B.pack_block_weights(w) for w in wts]
+    wts_packed = [B.pack_block_weights(w, fold_ln1=not args.no_fold_ln1) for w in wts]
     structs = [B.block_weights_struct(w) for w in wts_packed]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)

@@ -180,6 +180,31 @@ int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed,
  * 2 (256x128) has no packed form (SSAM_EUNSUPPORTED when forced). */
 int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream);
 
+/* LayerNorm folded into the Linear that follows it (SAM's pre-LN block: qkv =
+ * Linear(LN1(x)), the input of Stripe-Sort attention, Sec. 4.1).  With
+ * mean_m, rstd_m the statistics of row m,
+ *   Linear(LN(x))[m][n] = rstd_m * (sum_k x[m][k] Wf[n][k] - mean_m * colsum[n]) + bias_f[n],
+ *   Wf[n][k] = bf16(W[n][k] * gamma[k]),  colsum[n] = sum_k Wf[n][k] (of the stored
+ *   values, fp32),  bias_f[n] = bias[n] + sum_k beta[k] W[n][k],
+ * so the normalised rows are never written: the statistics are one read of x
+ * and the contraction reads x itself.
+ * ssam_ln_stats: x dev bf16 [rows][D] contiguous -> stats dev fp32 [rows][2] =
+ *   { rstd, -rstd * mean } (biased variance, two-pass fp32); D % 8 == 0, D <= 2048.
+ * ssam_fold_ln_weight: W dev bf16 [N][K] (row stride ldw), bias [N], gamma, beta [K]
+ *   dev fp32 -> Wf dev bf16 [N][K] contiguous (give it to ssam_pack_weight), colsum,
+ *   bias_f dev fp32 [N].  One-time weight preparation.
+ * ssam_linear_ln: C[dst(m)][:] = the formula above for row m of x (dev bf16, row
+ *   stride ldx), Wfp = ssam_pack_weight(Wf); dst(m) as for SSAM_EPI_BIAS_SCATTER
+ *   (row_map required; entries outside [0, dst_rows_per_batch) skip the row).
+ *   M % 128 == 0, N % 256 == 0, K % 64 == 0 (else SSAM_EUNSUPPORTED). */
+int ssam_ln_stats(const void *x, float *stats, long rows, int D, float eps, void *stream);
+int ssam_fold_ln_weight(const void *W, int ldw, const float *bias, const float *gamma, const float *beta,
+                        void *Wf, float *colsum, float *bias_f, int N, int K, void *stream);
+int ssam_linear_ln(const void *x, int ldx, const float *stats, const void *Wfp, const float *colsum,
+                   const float *bias_f, void *C, int ldc, int M, int N, int K,
+                   const int32_t *row_map, int rows_per_batch, int map_batch_stride, int dst_rows_per_batch,
+                   void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Stripe-Sort attention (App. A.1, Alg. 1)                                  */
 /* ------------------------------------------------------------------------- */
@@ -260,6 +285,14 @@ typedef struct ssam_block_weights {     /* every pointer: dev */
     const void *w2;                     /* bf16 [D][Dm]                              */
     const float *b2;                    /* [D] fp32                                  */
     int packed;                         /* != 0: wqkv, wproj, w1, w2 are in the fragment order of ssam_pack_weight */
+    int fold_ln1;                       /* != 0 (needs packed != 0): LN1 is folded into the qkv contraction, see
+                                           ssam_fold_ln_weight: wqkv is the packed form of its Wf, qkv_colsum and
+                                           bqkv_folded are its other outputs; bqkv stays the plain bias (the
+                                           padding slots of a window are zero rows AFTER LN1) and ln1_g, ln1_b
+                                           are not read.  B*g*g % 128 == 0 and 3D % 256 == 0, else
+                                           SSAM_EUNSUPPORTED. */
+    const float *qkv_colsum;            /* [3D] fp32 (fold_ln1 only)                 */
+    const float *bqkv_folded;           /* [3D] fp32 (fold_ln1 only)                 */
 } ssam_block_weights;
 
 typedef struct ssam_block_cfg {

@@ -32,7 +32,8 @@ _WEIGHT_POINTERS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj",
 
 
 class BlockWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_POINTERS] + [("packed", C.c_int)]
+    _fields_ = ([(n, C.c_void_p) for n in _WEIGHT_POINTERS] + [("packed", C.c_int), ("fold_ln1", C.c_int),
+                ("qkv_colsum", C.c_void_p), ("bqkv_folded", C.c_void_p)])
 
 
 class BlockCfg(C.Structure):
@@ -299,22 +300,63 @@ def ssam_pack_weight(W, Wp=None):
     return Wp
 
 
-def pack_block_weights(wt: dict) -> dict:
-    """Device weight dict -> the same with the four Linear weights in fragment order (flagged 'packed')."""
+def ssam_ln_stats(x, eps=1e-6):
+    """x: [..., D] bf16 contiguous -> [rows, 2] fp32 {rstd, -rstd*mean}."""
+    _dev(x, torch.bfloat16, "x")
+    D = x.shape[-1]
+    rows = x.numel() // D
+    stats = torch.empty((rows, 2), dtype=torch.float32, device=x.device)
+    _check("ssam_ln_stats", lib().ssam_ln_stats(_bf(x, "x"), _f32(stats, "stats"), C.c_long(rows), C.c_int(D),
+                                                  C.c_float(eps), _stream()))
+    return stats
+
+
+def ssam_fold_ln_weight(W, bias, gamma, beta):
+    """-> (Wf [N,K] bf16, colsum [N] fp32, bias_f [N] fp32), see the header."""
+    _dev(W, torch.bfloat16, "W")
+    N, K = W.shape
+    Wf = torch.empty((N, K), dtype=torch.bfloat16, device=W.device)
+    colsum = torch.empty(N, dtype=torch.float32, device=W.device)
+    bias_f = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check("ssam_fold_ln_weight", lib().ssam_fold_ln_weight(
+        _bf(W, "W"), C.c_int(K), _f32(bias, "bias"), _f32(gamma, "gamma"), _f32(beta, "beta"), _bf(Wf, "Wf"),
+        _f32(colsum, "colsum"), _f32(bias_f, "bias_f"), C.c_int(N), C.c_int(K), _stream()))
+    return Wf, colsum, bias_f
+
+
+def ssam_linear_ln(x, stats, Wfp, colsum, bias_f, out, row_map, rows_per_batch, map_batch_stride, dst_rows_per_batch):
+    """out[dst(m)] = Linear(LN(x[m])) with the LayerNorm folded in; x [M,K], Wfp packed [N,K], out [rows,N]."""
+    _dev(x, torch.bfloat16, "x"); _dev(out, torch.bfloat16, "out")
+    M, K = x.shape
+    N = Wfp.shape[0]
+    _check("ssam_linear_ln", lib().ssam_linear_ln(
+        _bf(x, "x"), C.c_int(K), _f32(stats, "stats"), _bf(Wfp, "Wfp"), _f32(colsum, "colsum"), _f32(bias_f, "bias_f"),
+        _bf(out, "out"), C.c_int(out.shape[-1]), C.c_int(M), C.c_int(N), C.c_int(K), _i32(row_map, "row_map"),
+        C.c_int(rows_per_batch), C.c_int(map_batch_stride), C.c_int(dst_rows_per_batch), _stream()))
+    return out
+
+
+def pack_block_weights(wt: dict, fold_ln1=False) -> dict:
+    """Device weight dict -> the same with the four Linear weights in fragment order (flagged 'packed').
+    fold_ln1: wqkv becomes the packed LN1-folded weight (ssam_fold_ln_weight), with its column sums and bias."""
     out = dict(wt)
     for k in _PACKABLE:
         out[k] = ssam_pack_weight(wt[k])
     out["packed"] = True
+    if fold_ln1:
+        Wf, colsum, bias_f = ssam_fold_ln_weight(wt["wqkv"], wt["bqkv"], wt["ln1_g"], wt["ln1_b"])
+        out["wqkv"] = ssam_pack_weight(Wf)
+        out["qkv_colsum"], out["bqkv_folded"], out["fold_ln1"] = colsum, bias_f, True
     return out
 
 
-def upload_block_weights(wdict: dict, device="cuda", pack=False) -> dict:
+def upload_block_weights(wdict: dict, device="cuda", pack=False, fold_ln1=False) -> dict:
     """numpy fp32 dict (bf16-representable values) -> device tensors in the ABI's dtypes."""
     out = {}
     for k, v in wdict.items():
         t = torch.from_numpy(np.ascontiguousarray(v))
         out[k] = t.to(device=device, dtype=torch.bfloat16 if k in _BF16_FIELDS else torch.float32).contiguous()
-    return pack_block_weights(out) if pack else out
+    return pack_block_weights(out, fold_ln1=fold_ln1) if pack else out
 
 
 def block_weights_struct(wt: dict) -> BlockWeights:
@@ -325,6 +367,11 @@ def block_weights_struct(wt: dict) -> BlockWeights:
         _dev(t, want, name)
         setattr(s, name, t.data_ptr())
     s.packed = 1 if wt.get("packed") else 0
+    s.fold_ln1 = 1 if wt.get("fold_ln1") else 0
+    if s.fold_ln1:
+        for name in ("qkv_colsum", "bqkv_folded"):
+            _dev(wt[name], torch.float32, name)
+            setattr(s, name, wt[name].data_ptr())
     return s
 
 

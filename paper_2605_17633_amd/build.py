@@ -93,7 +93,7 @@ def build_library(force: bool = True, jobs: int = 5) -> str:
                 f.write(f"{src} {k['name']} vgprs={k.get('VGPRs', -1)} agprs={k.get('AGPRs', -1)} "
                         f"scratch={k.get('ScratchSize', -1)} spill={k.get('VGPRs Spill', -1)} "
                         f"occupancy={k.get('Occupancy', -1)} lds={k.get('LDS Size', -1)}\n")
-                if k.get("VGPRs Spill", 0) > 0 and ("gemm_bf16_nt_kernel" in k["name"] or "attn_" in k["name"]):
+                if k.get("VGPRs Spill", 0) > 0 and ("gemm_bf16_nt_" in k["name"] or "attn_" in k["name"]):
                     spilled.append(f"{k['name']}: {k['VGPRs Spill']} VGPRs spilled")
     if spilled:
         raise RuntimeError("hot kernels spill registers:\n" + "\n".join(spilled))

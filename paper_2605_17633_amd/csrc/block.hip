@@ -13,6 +13,9 @@ int ssam_compact_slots(const int32_t *table, int table_batch_stride, int B, int 
                        int32_t *real_slot, int32_t *real_spatial, int32_t *slot_row, int32_t *pad_slot, hipStream_t st);
 int ssam_fill_bias_rows(void *C, long ldc, const float *bias, int n_cols, const int32_t *pad_slot, int npad,
                         int rows_per_batch, int B, hipStream_t st);
+int ssam_invert_table(const int32_t *table, int table_batch_stride, int B, int Nout, int N, int32_t *inv, hipStream_t st);
+int ssam_linear_ln_impl(const void *A, const float *stats, const void *Wfp, const float *colsum, const float *bias_f,
+                        void *C, int M, int N, int K, const GemmLd &ld, const GemmRowMap &rm, hipStream_t st);
 
 namespace {
 
@@ -67,6 +70,25 @@ PadTables carve_pad_tables(unsigned char *p, int B, const BlockGeom &g)
     p += align256((size_t)B * g.Nout * 4);
     t.pad_slot = (int32_t *)p;
     return t;
+}
+
+// Tables of a block that depend only on its gather table, kept behind everything a block writes so that a stack
+// builds them once: the padding tables (windowed blocks with padding), then slot_of [B][N], the scan-order slot of
+// every token (the inverse of the gather table; the folded-LN1 qkv contraction walks the tokens in memory order
+// and stores each row to its slot).
+size_t block_tables_bytes(int B, const BlockGeom &g) { return pad_tables_bytes(B, g) + align256((size_t)B * g.N * 4); }
+
+int32_t *slot_of_table(unsigned char *tables, int B, const BlockGeom &g) { return (int32_t *)(tables + pad_tables_bytes(B, g)); }
+
+int build_block_tables(const ssam_block_cfg *cfg, const BlockGeom &g, const int32_t *gather_table, unsigned char *tables, hipStream_t st)
+{
+    const int per_image = cfg->content_order != 0;
+    if (g.Nout != g.N) {
+        const PadTables pt = carve_pad_tables(tables, cfg->B, g);
+        int rc = ssam_compact_slots(gather_table, per_image ? g.Nout : 0, cfg->B, g.Nout, g.N, pt.real_slot, pt.real_spatial, pt.slot_row, pt.pad_slot, st);
+        if (rc != SSAM_OK) return rc;
+    }
+    return ssam_invert_table(gather_table, per_image ? g.Nout : 0, per_image ? cfg->B : 1, g.Nout, g.N, slot_of_table(tables, cfg->B, g), st);
 }
 
 }  // namespace
@@ -133,19 +155,24 @@ extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
 {
     BlockGeom g;
     if (!block_geom(cfg, g)) return 0;
-    return block_core_bytes(cfg, g) + pad_tables_bytes(cfg->B, g);
+    return block_core_bytes(cfg, g) + block_tables_bytes(cfg->B, g);
 }
 
+// tables: this block's block_tables_bytes region; tables_ready: a stack has built it already
 static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
                               const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
-                              void *workspace, size_t workspace_bytes, void **qkv_events, bool pad_tables_ready, void *stream)
+                              void *workspace, size_t workspace_bytes, void **qkv_events, unsigned char *tables,
+                              bool tables_ready, void *stream)
 {
     BlockGeom g;
     if (!x || !w || !gather_table || !sigma || !keep_idx || !workspace || !block_geom(cfg, g)) return SSAM_EINVAL;
     if (!(cfg->r > 0.0) || cfg->r > 1.0) return SSAM_EINVAL;
     if (!ssam_aligned16(workspace) || !ssam_aligned16(x)) return SSAM_EINVAL;
     if (cfg->D % 128 != 0 || cfg->Dm % 128 != 0) return SSAM_EUNSUPPORTED;
-    if (workspace_bytes < ssam_encoder_block_workspace_bytes(cfg)) return SSAM_EWORKSPACE;
+    if (!tables) {
+        if (workspace_bytes < ssam_encoder_block_workspace_bytes(cfg)) return SSAM_EWORKSPACE;
+        tables = (unsigned char *)workspace + block_core_bytes(cfg, g);
+    }
     const int B = cfg->B, D = cfg->D;
     const int rows = B * g.Nout;                               // slots of the scan-order layout (with padding)
     const bool padded = g.Nout != g.N;
@@ -160,13 +187,36 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     const bool packed = w->packed != 0;
     GemmRowMap none = { nullptr, 1, 0, 1 };
     int rc;
-
-    if (!padded) {
-        rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
+    const bool fold = w->fold_ln1 != 0;
+    if (fold) {
+        if (!packed || !w->qkv_colsum || !w->bqkv_folded) return SSAM_EINVAL;
+        if (crows % 128 != 0 || (3 * D) % 256 != 0) return SSAM_EUNSUPPORTED;
+    }
+    if (!tables_ready) {
+        rc = build_block_tables(cfg, g, gather_table, tables, st);
+        if (rc != SSAM_OK) return rc;
+    }
+    if (fold) {
+        // LN1 folded into the qkv contraction: only the statistics of every token are taken here (parked at the
+        // start of u, which nothing else uses before attention writes its output there); the contraction reads
+        // the tokens where they lie and stores every row to its scan-order slot
+        float *stats = (float *)u;
+        rc = ssam_ln_stats(x, stats, crows, D, cfg->eps, stream);
         if (rc != SSAM_OK) return rc;
         if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-        rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        GemmRowMap to_slot = { slot_of_table(tables, B, g), g.N, per_image ? g.N : 0, g.Nout };
+        rc = ssam_linear_ln_impl(x, stats, w->wqkv, w->qkv_colsum, w->bqkv_folded, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, to_slot, st);
         if (rc != SSAM_OK) return rc;
+    }
+
+    if (!padded) {
+        if (!fold) {
+            rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
+            if (rc != SSAM_OK) return rc;
+            if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+            rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, rows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
+            if (rc != SSAM_OK) return rc;
+        }
         if (qkv_events && qkv_events[1] && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
         rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, nullptr,
                                    B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
@@ -181,17 +231,15 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
         // [B*N][D] matrix in scan order, the qkv contraction runs on those rows and scatters them to their
         // slots, the padding slots are filled with the bias, attention writes only the real queries (compact
         // again), and the proj contraction scatters them back to spatial order.
-        const PadTables pt = carve_pad_tables(ws + block_core_bytes(cfg, g), B, g);
-        if (!pad_tables_ready) {
-            rc = ssam_compact_slots(gather_table, per_image ? g.Nout : 0, B, g.Nout, g.N, pt.real_slot, pt.real_spatial, pt.slot_row, pt.pad_slot, st);
+        const PadTables pt = carve_pad_tables(tables, B, g);
+        if (!fold) {
+            rc = ssam_ln_gather(x, pt.real_spatial, g.N, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.N, D, stream);
+            if (rc != SSAM_OK) return rc;
+            if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
+            GemmRowMap to_slot = { pt.real_slot, g.N, g.N, g.Nout };
+            rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS_SCATTER, to_slot, 0, split, GEMM_SPLIT_WS_BYTES, st);
             if (rc != SSAM_OK) return rc;
         }
-        rc = ssam_ln_gather(x, pt.real_spatial, g.N, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.N, D, stream);
-        if (rc != SSAM_OK) return rc;
-        if (qkv_events && qkv_events[0] && hipEventRecord((hipEvent_t)qkv_events[0], st) != hipSuccess) return SSAM_EHIP;
-        GemmRowMap to_slot = { pt.real_slot, g.N, g.N, g.Nout };
-        rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS_SCATTER, to_slot, 0, split, GEMM_SPLIT_WS_BYTES, st);
-        if (rc != SSAM_OK) return rc;
         rc = ssam_fill_bias_rows(qkv, 3L * D, w->bqkv, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
         if (rc != SSAM_OK) return rc;
         if (qkv_events && qkv_events[1] && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
@@ -211,17 +259,21 @@ extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ss
                                   const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
                                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, false, stream);
+    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, nullptr, false, stream);
 }
 
 extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global)
 {
-    size_t a = cfg_local ? ssam_encoder_block_workspace_bytes(cfg_local) : 0;
-    size_t b = cfg_global ? ssam_encoder_block_workspace_bytes(cfg_global) : 0;
+    // what either kind of block writes, then the tables of the windowed blocks, then those of the global blocks
+    BlockGeom gl, gg;
+    const bool l = cfg_local && block_geom(cfg_local, gl), g = cfg_global && block_geom(cfg_global, gg);
+    if ((cfg_local && !l) || (cfg_global && !g)) return 0;
+    size_t core = 0, tables = 0;
+    if (l) { core = block_core_bytes(cfg_local, gl); tables += block_tables_bytes(cfg_local->B, gl); }
+    if (g) { size_t c = block_core_bytes(cfg_global, gg); core = c > core ? c : core; tables += block_tables_bytes(cfg_global->B, gg); }
     const ssam_block_cfg *c = cfg_local ? cfg_local : cfg_global;
     size_t s = c ? align256(ssam_score_tokens_workspace_bytes(c->B, c->g, c->g)) : 0;
-    size_t m = a > b ? a : b;
-    return m > s ? m : s;
+    return (core > s ? core : s) + tables;
 }
 
 extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, const uint8_t *is_global, int n_blocks,
@@ -261,23 +313,35 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
     }
     rc = ssam_select_tokens(scores, keep_idx, c0->B, c0->g * c0->g, c0->K, stream);
     if (rc != SSAM_OK) return rc;
-    // the padding tables of the windowed blocks are the same for every block: built once, behind everything
-    // either kind of block writes (the global blocks' extent is smaller than the windowed ones')
-    BlockGeom gl;
-    if (any_local && block_geom(cfg_local, gl) && gl.Nout != gl.N) {
-        BlockGeom gg;
-        if (any_global && (!block_geom(cfg_global, gg) || block_core_bytes(cfg_global, gg) > block_core_bytes(cfg_local, gl)))
-            return SSAM_EINVAL;
-        const PadTables pt = carve_pad_tables((unsigned char *)workspace + block_core_bytes(cfg_local, gl), cfg_local->B, gl);
-        rc = ssam_compact_slots(window_table, cfg_local->content_order ? gl.Nout : 0, cfg_local->B, gl.Nout, gl.N,
-                                pt.real_slot, pt.real_spatial, pt.slot_row, pt.pad_slot, (hipStream_t)stream);
+    // the tables of either kind of block are the same for every block of that kind: built once, behind everything
+    // the blocks write
+    BlockGeom gl, gg;
+    size_t core = 0;
+    if (any_local) { if (!block_geom(cfg_local, gl)) return SSAM_EINVAL; core = block_core_bytes(cfg_local, gl); }
+    if (any_global) {
+        if (!block_geom(cfg_global, gg)) return SSAM_EINVAL;
+        size_t c = block_core_bytes(cfg_global, gg);
+        core = c > core ? c : core;
+    }
+    {
+        size_t sc = align256(ssam_score_tokens_workspace_bytes(c0->B, c0->g, c0->g));
+        core = core > sc ? core : sc;
+    }
+    unsigned char *tables_local = (unsigned char *)workspace + core;
+    unsigned char *tables_global = tables_local + (any_local ? block_tables_bytes(cfg_local->B, gl) : 0);
+    if (any_local) {
+        rc = build_block_tables(cfg_local, gl, window_table, tables_local, (hipStream_t)stream);
+        if (rc != SSAM_OK) return rc;
+    }
+    if (any_global) {
+        rc = build_block_tables(cfg_global, gg, global_table, tables_global, (hipStream_t)stream);
         if (rc != SSAM_OK) return rc;
     }
     for (int i = 0; i < n_blocks; ++i) {
         void **ev = qkv_events ? qkv_events + 2 * i : nullptr;
         rc = is_global[i]
-                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, workspace_bytes, ev, true, stream)
-                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, workspace_bytes, ev, true, stream);
+                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, core, ev, tables_global, true, stream)
+                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, core, ev, tables_local, true, stream);
         if (rc != SSAM_OK) return rc;
     }
     return SSAM_OK;

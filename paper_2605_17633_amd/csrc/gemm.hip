@@ -206,6 +206,37 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
     }
 }
 
+// The contraction with the LayerNorm of its A rows folded in (see GemmFold): 128x256 tiles, packed weights,
+// mapped store; M a multiple of 128 and N of 256, so there are no left-over tiles.
+int ssam_linear_ln_impl(const void *A, const float *stats, const void *Wfp, const float *colsum, const float *bias_f,
+                        void *C, int M, int N, int K, const GemmLd &ld, const GemmRowMap &rm, hipStream_t st)
+{
+    constexpr size_t lds = gemm_lds_bytes<128, 256, 1, 4, true>();
+    static_assert(lds <= 64 * 1024, "default LDS limit");
+    GemmTileRange tr = { M / 128, N / 256, 0, (M / 128) * (N / 256) };
+    const GemmFold fold = { reinterpret_cast<const float2 *>(stats), colsum };
+    const int per_xcd = ssam_div_up(tr.tile_count, 8);
+    hipLaunchKernelGGL((gemm_bf16_nt_lnf_kernel<128, 256, SSAM_EPI_BIAS_SCATTER, 1, 4>), dim3(per_xcd * 8), dim3(256), lds, st,
+                       (const bf16 *)A, (const bf16 *)Wfp, bias_f, (bf16 *)C, M, N, K, ld, tr, rm, fold);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_linear_ln(const void *x, int ldx, const float *stats, const void *Wfp, const float *colsum,
+                              const float *bias_f, void *C, int ldc, int M, int N, int K,
+                              const int32_t *row_map, int rows_per_batch, int map_batch_stride, int dst_rows_per_batch,
+                              void *stream)
+{
+    if (!x || !stats || !Wfp || !colsum || !bias_f || !C || !row_map || M <= 0 || N <= 0 || K <= 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(x) || !ssam_aligned16(Wfp) || !ssam_aligned16(colsum) || !ssam_aligned16(bias_f) || !ssam_aligned16(C) ||
+        ((uintptr_t)stats & 7))
+        return SSAM_EINVAL;
+    if (ldx < K || ldc < N || ldx % 8 || ldc % 8 || rows_per_batch <= 0 || map_batch_stride < 0 || dst_rows_per_batch <= 0) return SSAM_EINVAL;
+    if (M % 128 != 0 || N % 256 != 0 || K % GEMM_BK != 0) return SSAM_EUNSUPPORTED;
+    const GemmRowMap rm = { row_map, rows_per_batch, map_batch_stride, dst_rows_per_batch };
+    return ssam_linear_ln_impl(x, stats, Wfp, colsum, bias_f, C, M, N, K, GemmLd{ ldx, K, ldc }, rm, (hipStream_t)stream);
+}
+
 extern "C" size_t ssam_linear_workspace_bytes(void) { return GEMM_SPLIT_WS_BYTES; }
 
 __global__ void __launch_bounds__(256)

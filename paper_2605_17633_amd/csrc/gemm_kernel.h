@@ -43,7 +43,7 @@ template <int BM, int BN, int WGM = 2, int WGN = 2, bool WPACK = false>
 constexpr size_t gemm_lds_bytes()
 {
     size_t pipe = (size_t)2 * (BM + (WPACK ? 0 : BN)) * GEMM_BK * sizeof(bf16);
-    size_t epi = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) + BM * sizeof(int);   // staging + scatter rows
+    size_t epi = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) + BM * (sizeof(int) + sizeof(float2));   // staging + scatter rows + row statistics
     return pipe > epi ? pipe : epi;
 }
 
@@ -66,6 +66,14 @@ constexpr int GEMM_EPI_PARTIAL = 8;   // internal: store the fp32 tile of one K 
 constexpr int GEMM_GROUP_M = 8;
 constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)32 << 20;   // workspace that lets the left-over launch cut K
 
+// LayerNorm folded into the contraction that follows it (LNF instantiations): A holds the rows before the
+// normalisation, W holds W*diag(gamma), and the epilogue finishes  rstd_m * (acc - mean_m * colsum_n) + bias_n
+// with bias_n = b_n + sum_k beta_k W[n][k].
+struct GemmFold {
+    const float2 *stats;      // [M] per row of A: { rstd, -rstd * mean }
+    const float *colsum;      // [N] sum over k of the folded weight as stored (bf16 values, fp32 sum)
+};
+
 struct GemmSplit {
     float *partial;           // [tile_count*SUB_M*SUB_N][parts][BM][BN] fp32, NULL unless GEMM_EPI_PARTIAL
     int parts;                // K ranges per tile (1 otherwise); parts <= K/64
@@ -86,12 +94,13 @@ __device__ __forceinline__ void gemm_tile_origin(const GemmTileRange &tr, int t,
 
 // The workgroup's work, as a function of its index `bid` in the launch (the kernels below pass blockIdx.x, or
 // blockIdx.x less the workgroups of another kind that share the launch).
-template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false, bool LNF = false>
 __device__ __forceinline__ void
 gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                   bf16 *C, int M, int N, int K, const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm,
-                  const GemmSplit &sp, int bid)
+                  const GemmSplit &sp, int bid, const GemmFold &fold = GemmFold{ nullptr, nullptr })
 {
+    static_assert(!LNF || EPI != GEMM_EPI_PARTIAL, "the folded LayerNorm is finished by the epilogue proper");
     constexpr int THREADS = 64 * WGM * WGN, RSTEP = THREADS / 8;   // waves in a WGM x WGN grid; rows staged per pass
     constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
     constexpr int A_LOADS = BM * 8 / THREADS, B_LOADS = BN * 8 / THREADS;
@@ -332,22 +341,38 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         bv[4] = x1.x; bv[5] = x1.y; bv[6] = x1.z; bv[7] = x1.w;
     }
     const bool col_ok = ncol < N;               // N % 8 == 0: a lane's 8 columns are all inside or all outside
+    constexpr int PASSES = 32 / RPP;
+    float sv[LNF ? 8 : 1];
+    if constexpr (LNF) {
+        const float4 *c4 = reinterpret_cast<const float4 *>(fold.colsum + (ncol < N ? ncol : 0));
+        float4 x0 = c4[0], x1 = c4[1];
+        sv[0] = x0.x; sv[1] = x0.y; sv[2] = x0.z; sv[3] = x0.w;
+        sv[4] = x1.x; sv[5] = x1.y; sv[6] = x1.z; sv[7] = x1.w;
+    }
     // The scatter epilogue is a read-modify-write of rows of the residual stream.  Its destination rows
     // are looked up once per tile (one row per thread, parked in LDS behind the staging regions) and the
     // old values of a whole 32-row slice are requested before the slice is staged, so that the slice pays
     // one memory round trip instead of one per pass.
-    constexpr int PASSES = 32 / RPP;
     int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + WGM * WGN * 32 * EPS);   // [BM], -1 = skip
     constexpr bool MAPPED = EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER;
-    if (MAPPED) {
+    float2 *row_stats = reinterpret_cast<float2 *>(dst_row + BM);    // [BM] { rstd, -rstd*mean } (LNF), parked like dst_row
+    if (MAPPED || LNF) {
         int mine = -1;
+        float2 mine_stats = { 0.f, 0.f };
         if (tid < BM && m0 + tid < M) {
-            int m = m0 + tid, b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
-            int idx = rm.map[(long)b * rm.map_batch_stride + p];
-            if (idx >= 0 && idx < rm.dst_rows_per_batch) mine = b * rm.dst_rows_per_batch + idx;
+            int m = m0 + tid;
+            if constexpr (LNF) mine_stats = fold.stats[m];
+            if (MAPPED) {
+                int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
+                int idx = rm.map[(long)b * rm.map_batch_stride + p];
+                if (idx >= 0 && idx < rm.dst_rows_per_batch) mine = b * rm.dst_rows_per_batch + idx;
+            }
         }
         __syncthreads();                        // every wave is done with the pipeline buffers
-        if (tid < BM) dst_row[tid] = mine;
+        if (tid < BM) {
+            if (MAPPED) dst_row[tid] = mine;
+            if constexpr (LNF) row_stats[tid] = mine_stats;
+        }
     }
     __syncthreads();                            // pipeline buffers free for staging; dst_row visible
     // The bias values must have landed before the first store pass: a pass that first touched them behind its
@@ -355,6 +380,10 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     // stores of the passes before it, and every pass would then wait for the previous pass's store to complete.
 #pragma unroll
     for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(bv[e]));
+    if constexpr (LNF) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(sv[e]));
+    }
     // From here on a wave touches only its own staging region: LDS operations of one wave execute in
     // order, so the slices need no workgroup barrier (which would also wait for the previous slice's
     // global stores); wavefront fences keep the compiler from reordering the LDS accesses.
@@ -401,8 +430,15 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
                 dst[1] = y1;
                 continue;
             }
-            float v[8] = { y0.x + bv[0], y0.y + bv[1], y0.z + bv[2], y0.w + bv[3],
-                           y1.x + bv[4], y1.y + bv[5], y1.z + bv[6], y1.w + bv[7] };
+            float v[8] = { y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w };
+            if constexpr (LNF) {
+                const float2 t = row_stats[wm + i * 32 + row];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] * t.x + (t.y * sv[e] + bv[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += bv[e];
+            }
             if (EPI == SSAM_EPI_BIAS_GELU) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
@@ -434,6 +470,16 @@ gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, cons
                     bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
 {
     gemm_bf16_nt_body<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, sp, (int)blockIdx.x);
+}
+
+// The same workgroup with the LayerNorm of its A rows folded in (see GemmFold).
+template <int BM, int BN, int EPI, int WGM, int WGN>
+__global__ void __launch_bounds__(64 * WGM * WGN, (BN == 256 && WGM * WGN == 4) ? 2 : 1)
+gemm_bf16_nt_lnf_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
+                        bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmFold fold)
+{
+    const GemmSplit whole = { nullptr, 1 };
+    gemm_bf16_nt_body<BM, BN, EPI, 1, 1, WGM, WGN, true, true>(A, W, bias, C, M, N, K, ld, tr, rm, whole, (int)blockIdx.x, fold);
 }
 
 // Whole rounds and left-over tiles in ONE launch (both kinds of workgroup have 256 threads): the first `n_tail`

@@ -124,6 +124,82 @@ ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, i
     }
 }
 
+// ---------------------------------------------------------------- LN statistics only
+// The statistics half of the LayerNorm above, for a contraction that has the normalisation folded in:
+// one wave per row, stats[row] = { rstd, -rstd * mean } (same two-pass fp32 arithmetic as ln_gather_kernel).
+template <int MAXC>
+__global__ void __launch_bounds__(256)
+ln_stats_kernel(const uint4 *__restrict__ x, float2 *__restrict__ stats, long rows, int chunks, float eps)
+{
+    int lane = threadIdx.x & 63;
+    long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const uint4 *xrow = x + row * chunks;
+    uint4 raw[MAXC];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) raw[i] = xrow[min(lane + 64 * i, chunks - 1)];
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        unpack_bf16x8(raw[i], v[i]);
+        if (lane + 64 * i < chunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[i][e];
+        }
+    }
+    int D = chunks * 8;
+    float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        if (lane + 64 * i < chunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { float t = v[i][e] - mean; q += t * t; }
+        }
+    }
+    float inv = rsqrtf(wave_sum(q) / (float)D + eps);
+    if (lane == 0) stats[row] = make_float2(inv, -inv * mean);
+}
+
+// Weight side of the fold: one wave per output channel n.
+//   Wf[n][k] = bf16(W[n][k] * gamma[k]);  colsum[n] = sum_k Wf[n][k] (the stored values);  bias_f[n] = bias[n] + sum_k beta[k] W[n][k]
+__global__ void __launch_bounds__(256)
+fold_ln_weight_kernel(const bf16 *__restrict__ W, int ldw, const float *__restrict__ bias, const float *__restrict__ gamma,
+                      const float *__restrict__ beta, bf16 *__restrict__ Wf, float *__restrict__ colsum,
+                      float *__restrict__ bias_f, int N, int K)
+{
+    int lane = threadIdx.x & 63;
+    int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (n >= N) return;
+    float cs = 0.f, bs = 0.f;
+    for (int c = lane; c < K / 8; c += 64) {
+        float w[8], o[8];
+        unpack_bf16x8(*reinterpret_cast<const uint4 *>(W + (long)n * ldw + c * 8), w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { o[e] = w[e] * gamma[c * 8 + e]; bs += beta[c * 8 + e] * w[e]; }
+        uint4 packed = pack_bf16x8(o);
+        *reinterpret_cast<uint4 *>(Wf + (long)n * K + c * 8) = packed;
+        unpack_bf16x8(packed, o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cs += o[e];
+    }
+    cs = wave_sum(cs);
+    bs = wave_sum(bs);
+    if (lane == 0) { colsum[n] = cs; bias_f[n] = bias[n] + bs; }
+}
+
+// inv[b][table[b][p]] = p for every slot p that holds a token (table entries < 0 are padding)
+__global__ void __launch_bounds__(256)
+invert_table_kernel(const int32_t *__restrict__ table, int table_batch_stride, int Nout, int N, int32_t *__restrict__ inv, int total)
+{
+    int id = blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    int b = id / Nout, p = id - b * Nout;
+    int s = table[(long)b * table_batch_stride + p];
+    if (s >= 0 && s < N) inv[(long)b * N + s] = p;
+}
+
 // ---------------------------------------------------------------- scores
 // channel sum of every token: one wave per token
 __global__ void __launch_bounds__(256)
@@ -488,6 +564,45 @@ int ssam_fill_bias_rows(void *C, long ldc, const float *bias, int n_cols, const 
     if (total <= 0) return SSAM_OK;
     hipLaunchKernelGGL(fill_bias_rows_kernel, dim3(ssam_div_up(total, 4)), dim3(256), 0, st, (bf16 *)C, ldc, bias, n_cols,
                        pad_slot, npad, rows_per_batch, total);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_ln_stats(const void *x, float *stats, long rows, int D, float eps, void *stream)
+{
+    if (!x || !stats || rows <= 0 || D <= 0 || D % 8 != 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(x) || ((uintptr_t)stats & 7)) return SSAM_EINVAL;
+    if (D > 2048) return SSAM_EUNSUPPORTED;
+    int chunks = D / 8;
+    dim3 grid((unsigned)ssam_div_up(rows, 4)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (chunks <= 128)
+        hipLaunchKernelGGL(ln_stats_kernel<2>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+    else if (chunks <= 192)
+        hipLaunchKernelGGL(ln_stats_kernel<3>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+    else
+        hipLaunchKernelGGL(ln_stats_kernel<4>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_fold_ln_weight(const void *W, int ldw, const float *bias, const float *gamma, const float *beta,
+                                   void *Wf, float *colsum, float *bias_f, int N, int K, void *stream)
+{
+    if (!W || !bias || !gamma || !beta || !Wf || !colsum || !bias_f || N <= 0 || K <= 0 || ldw < K || ldw % 8) return SSAM_EINVAL;
+    if (!ssam_aligned16(W) || !ssam_aligned16(Wf)) return SSAM_EINVAL;
+    if (K % 8 != 0) return SSAM_EUNSUPPORTED;
+    hipLaunchKernelGGL(fold_ln_weight_kernel, dim3(ssam_div_up(N, 4)), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16 *)W, ldw, bias, gamma, beta, (bf16 *)Wf, colsum, bias_f, N, K);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+// internal (block composition): see invert_table_kernel
+int ssam_invert_table(const int32_t *table, int table_batch_stride, int B, int Nout, int N, int32_t *inv, hipStream_t st)
+{
+    const int total = B * Nout;
+    hipLaunchKernelGGL(invert_table_kernel, dim3(ssam_div_up(total, 256)), dim3(256), 0, st, table, table_batch_stride, Nout, N, inv, total);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }

@@ -38,7 +38,7 @@ def test_hot_kernels_keep_their_register_budget():
     for line in open(path):
         f = line.split()
         name, kv = f[1], dict(x.split("=") for x in f[2:])
-        if "gemm_bf16_nt_kernel" in name or "attn_" in name:
+        if "gemm_bf16_nt_" in name or "attn_" in name:
             hot.append((name, {k: int(v) for k, v in kv.items()}))
     assert len(hot) >= 20, "expected every GEMM and attention instantiation in the record"
     for name, r in hot:

@@ -173,10 +173,10 @@ def make_block_case(seed, B_, g, shape, ws, rho, scale_w=1.0):
     return wt, x, keep, K
 
 
-def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4):
+def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4, fold_ln1=False):
     B_, g = x.shape[0], x.shape[1]
     n = g * g
-    wd = B.upload_block_weights(wt)
+    wd = B.upload_block_weights(wt, pack=fold_ln1, fold_ln1=fold_ln1)
     cfg = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, ws, Bm, keep.shape[1], r)
     if ws > 0:
         table = dev_i32(oracle.window_table(g, ws, G))
@@ -213,6 +213,36 @@ def test_encoder_block_vit_b(name, g, ws, Bm, r, rho, scale_w):
         assert_close(got[b].reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest],
                      attn_only.reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest], f"{name}: attention-only rows b={b}",
                      stored=attn_only.reshape(g * g, -1)[rest], scale=np.abs(ref - x[b]).max())
+
+
+@pytest.mark.parametrize("name,ws,Bm,shape_name", [("windowed with padding", 14, 32, "VIT_B"), ("global", 0, 128, "VIT_B"),
+                                                  ("windowed with padding, d = 80", 14, 32, "VIT_H")])
+def test_encoder_block_folded_ln1(name, ws, Bm, shape_name):
+    """LN1 folded into the qkv contraction (statistics pass + contraction on the tokens where they lie + mapped
+    store) on a 32x32 grid, two images: against the oracle's block, to the bar of the plain path."""
+    announce("encoder_block folded LN1", name)
+    shape = getattr(inputs, shape_name)
+    g = 32
+    wt, x, keep, K = make_block_case(33, 2, g, shape, ws, 0.4)
+    # LayerNorm parameters away from (1, 0) so that a dropped gamma or beta shows
+    rng = np.random.default_rng(34)
+    wt["ln1_g"] = (1.0 + 0.3 * rng.normal(size=shape.D)).astype(np.float32)
+    wt["ln1_b"] = (0.2 * rng.normal(size=shape.D)).astype(np.float32)
+    got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4, fold_ln1=True)
+    ow = oracle.BlockWeights(**wt)
+    for b in range(x.shape[0]):
+        ref = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, 0.4, keep[b])
+        assert_close(got[b] - x[b], ref - x[b], f"folded LN1, {name}: block delta b={b}", stored=ref, updates=2)
+
+
+def test_encoder_block_folded_ln1_unsupported():
+    """Token counts that are not a multiple of the 128-row tile have no folded form."""
+    announce("encoder_block folded LN1 unsupported")
+    shape = inputs.VIT_B
+    wt, x, keep, K = make_block_case(35, 1, 28, shape, 14, 0.4)
+    with pytest.raises(B.SsamError) as e:
+        run_block_gpu(wt, x, keep, shape, 14, 32, 0.4, fold_ln1=True)
+    assert e.value.code == B.EUNSUPPORTED
 
 
 def test_encoder_block_vit_h_dims():

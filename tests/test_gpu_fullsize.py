@@ -55,6 +55,14 @@ def test_vit_h_block_full_size(ws, Bm, img):
     got = to_np(xd[img]).reshape(G, G, SHAPE.D)
     ref = oracle.encoder_block(x[img], oracle.BlockWeights(**wt), SHAPE.heads, ws, 4, Bm, R, keep_gpu[img])
     assert_close(got - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} image {img}", stored=ref, updates=2)
+    # the same block with packed weights and LN1 folded into the qkv contraction (the form bench.py times)
+    xf = torch.from_numpy(x.reshape(BATCH, n, SHAPE.D)).to(DEV).to(torch.bfloat16).contiguous()
+    wf = B.pack_block_weights(wd, fold_ln1=True)
+    B.ssam_encoder_block(xf, B.block_weights_struct(wf), cfg, table, sigma, keep)
+    torch.cuda.synchronize()
+    gotf = to_np(xf[img]).reshape(G, G, SHAPE.D)
+    assert_close(gotf - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} image {img}, folded LN1", stored=ref, updates=2)
+    del xf
     # every image was processed: finite, changed, and rows outside its keep-set differ from the input
     # only by the attention half (they are not touched by the MLP): checked on image 0 against the
     # attention-only oracle on a few sampled rows of one window / of the grid
@@ -81,8 +89,9 @@ def test_vit_h_encoder_full_depth():
     scores = torch.empty((BATCH, n), dtype=torch.float32, device=DEV)
     keep = torch.empty((BATCH, K), dtype=torch.int32, device=DEV)
     ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cfg_l, cfg_g), dtype=torch.uint8, device=DEV)
-    # the run that is compared with the oracle has the Linear weights in MFMA fragment order (the form bench.py times)
-    wps = [B.pack_block_weights(w) for w in wds]                    # kept alive: the structs hold raw pointers
+    # the run that is compared with the oracle has the Linear weights in MFMA fragment order and LN1 folded into
+    # the qkv contraction (the form bench.py times)
+    wps = [B.pack_block_weights(w, fold_ln1=True) for w in wds]      # kept alive: the structs hold raw pointers
     packed = [B.block_weights_struct(w) for w in wps]
     B.ssam_encoder_forward(xd, packed, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf)
     torch.cuda.synchronize()
@@ -100,7 +109,7 @@ def test_vit_h_encoder_full_depth():
     torch.cuda.synchronize()
     # (held to the bar of the whole stack, see below: a one-ulp difference in one block's bf16 output is carried
     # and rounded again by every later block, exactly as the difference to the oracle is)
-    assert_close(to_np(xd3), got_all.astype(np.float64), "row-major against packed weights, 32 blocks", tol=5e-2)
+    assert_close(to_np(xd3), got_all.astype(np.float64), "row-major against packed weights with folded LN1, 32 blocks", tol=5e-2)
     del xd2, xd3
     keep_gpu = keep[0].cpu().numpy()
     keep_ref = oracle.select_tokens(oracle.score_tokens(x[0]), K)

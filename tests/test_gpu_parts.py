@@ -403,3 +403,42 @@ def test_linear_rejects_unsupported():
     with pytest.raises(B.SsamError) as e:
         B.ssam_linear(A, W, b)
     assert e.value.code == B.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ LayerNorm folded into a contraction
+def test_ln_fold_pieces():
+    """ssam_ln_stats, ssam_fold_ln_weight and ssam_linear_ln against Linear(LN(x)) written out in fp64."""
+    announce("ln fold pieces")
+    rng = np.random.default_rng(70)
+    M, K, N = 1024, 768, 2304
+    x = inputs.bf16_round((rng.normal(size=(M, K)) * rng.uniform(0.3, 2.0, size=(M, 1)) + rng.normal(size=(M, 1))).astype(np.float32))
+    W = inputs.bf16_round((0.02 * rng.normal(size=(N, K))).astype(np.float32))
+    bias = (0.02 * rng.normal(size=N)).astype(np.float32)
+    gamma = (1.0 + 0.3 * rng.normal(size=K)).astype(np.float32)
+    beta = (0.2 * rng.normal(size=K)).astype(np.float32)
+    xd, Wd = dev_bf16(x), dev_bf16(W)
+    bd, gd, bed = (torch.from_numpy(a).to(DEV) for a in (bias, gamma, beta))
+    x64 = x.astype(np.float64)
+    mean, var = x64.mean(1), x64.var(1)
+    rstd = 1.0 / np.sqrt(var + 1e-6)
+    stats = B.ssam_ln_stats(xd, 1e-6)
+    got = stats.cpu().numpy()
+    np.testing.assert_allclose(got[:, 0], rstd, rtol=2e-6)
+    np.testing.assert_allclose(got[:, 1], -rstd * mean, rtol=2e-5, atol=2e-6)
+    Wf, colsum, bias_f = B.ssam_fold_ln_weight(Wd, bd, gd, bed)
+    Wf_ref = inputs.bf16_round((W * gamma[None, :]).astype(np.float32))       # one fp32 product, rounded once
+    assert np.array_equal(to_np(Wf), Wf_ref)
+    np.testing.assert_allclose(colsum.cpu().numpy(), Wf_ref.astype(np.float64).sum(1), rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(bias_f.cpu().numpy(), bias + (W.astype(np.float64) * beta[None, :]).sum(1), rtol=1e-5, atol=1e-6)
+    # rows stored through a map: two "images" of 512 rows, destination rows reversed within each image, 8 skipped
+    rmap = np.tile(np.arange(511, -1, -1, dtype=np.int32), 1)
+    rmap[:8] = -1
+    out = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.ssam_linear_ln(xd, stats, B.ssam_pack_weight(Wf), colsum, bias_f, out, dev_i32(rmap), 512, 0, 512)
+    torch.cuda.synchronize()
+    ref = ((x64 - mean[:, None]) * rstd[:, None] * gamma + beta) @ W.astype(np.float64).T + bias
+    got = to_np(out)
+    for b in range(2):
+        rows = np.arange(8, 512)
+        assert_close(got[b * 512 + rmap[rows]], ref[b * 512 + rows], f"folded linear image {b}")
+        assert np.all(got[b * 512 + np.arange(512 - 8, 512)] == 7.0)          # skipped rows' destinations untouched
