@@ -498,7 +498,8 @@ def main():
     achieved = avg_flops / (avg_ms * 1e-3) / 1e12
     rows_local = (-(-g // shape.ws)) ** 2 * shape.ws ** 2
     roofline = {
-        "kernel": "gemm_bf16_nt_kernel (qkv contraction, bias epilogue)",
+        "kernel": ("gemm_bf16_nt_kernel (qkv contraction, bias epilogue)" if args.no_fold_ln1 else
+                   "gemm_bf16_nt_lnf_kernel (qkv contraction with LN1 folded in, mapped store)"),
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": profile_traffic(shape.name),
         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": shape.depth,
