@@ -199,6 +199,8 @@ def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab,
     u = torch.empty((Bn, nW * S, D), dtype=bf, device=dev)
     ms = run(lambda: B.ssam_ln_gather(x0, wtab, 0, w0["ln1_g"], w0["ln1_b"], 1e-6, nW * S, y=u))
     parts["ln1_gather_windows"] = hbm(ms, 2.0 * Bn * (n + nW * S) * D)
+    ms = run(lambda: B.ssam_ln_stats(x0, 1e-6))      # what is left of LN1 as a pass when it is folded into the qkv contraction
+    parts["ln1_stats"] = hbm(ms, 2.0 * Bn * n * D)
     a2 = torch.empty((Bn, K, D), dtype=bf, device=dev)
     ms = run(lambda: B.ssam_ln_gather(x0, keep, K, w0["ln2_g"], w0["ln2_b"], 1e-6, K, y=a2))
     parts["ln2_gather_keep"] = hbm(ms, 2.0 * Bn * 2 * K * D)
