@@ -180,7 +180,7 @@ __device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const b
 //           bias terms are read at tq_h + (low half of krc) and tq_w + (high half of krc), in bytes
 //   FULL:   the chunk has all NB blocks (nb is not looked at: no per-block branches, no dummy scores)
 //   MIXADD: the column part of the bias is added by one mixed-precision fma (fp16 operand widened inside the
-//           instruction) instead of convert + add; costs registers the global kernel does not have at d = 80
+//           instruction) instead of convert + add
 constexpr float ATTN_LAG = 8.f;
 template <int D, int NB, bool RAGGED, bool FULL, typename TabT, bool MIXADD = false>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
@@ -653,9 +653,9 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             const int nb = min(NB, nblk - c0);
             const bool ragged = key0[NB - 1] + 32 > S;
             if (ragged)
-                attn_chunk_step<D, NB, true, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+                attn_chunk_step<D, NB, true, false, GlbTab, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             else
-                attn_chunk_step<D, NB, false, false, GlbTab>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
+                attn_chunk_step<D, NB, false, false, GlbTab, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
         }
     }
