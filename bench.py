@@ -345,7 +345,7 @@ def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
     shape = inputs.SHAPES[name]
     g = 64
     n = g * g
-    wts = [B.pack_block_weights(w, fold_ln1=True) for w in device_weights(torch, seed, shape, g, dev)]
+    wts = [B.pack_block_weights(w, fold_ln1=True, fold_kv_bias=True) for w in device_weights(torch, seed, shape, g, dev)]
     structs = [B.block_weights_struct(w) for w in wts]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)
@@ -424,7 +424,7 @@ def main():
     x0 = torch.from_numpy(x_host.reshape(Bn, n, shape.D)).to(dev).to(torch.bfloat16).contiguous()
     wts = device_weights(torch, args.seed + 1, shape, g, dev)
     # the four Linear weights of every block go into MFMA fragment order once, at load time (ssam_pack_weight)
-    wts_packed = [B.pack_block_weights(w, fold_ln1=not args.no_fold_ln1) for w in wts]
+    wts_packed = [B.pack_block_weights(w, fold_ln1=not args.no_fold_ln1, fold_kv_bias=not args.no_fold_ln1) for w in wts]
     structs = [B.block_weights_struct(w) for w in wts_packed]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)

@@ -200,6 +200,18 @@ int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *strea
 int ssam_ln_stats(const void *x, float *stats, long rows, int D, float eps, void *stream);
 int ssam_fold_ln_weight(const void *W, int ldw, const float *bias, const float *gamma, const float *beta,
                         void *Wf, float *colsum, float *bias_f, int N, int K, void *stream);
+/* Key and value biases taken out of the qkv contraction of a block (Alg. 1: the
+ * softmax runs over the keys of a query, so a term of the logit that is the same
+ * for every key, q.b_k, cancels; the probabilities of a query sum to one, so
+ * sum_j p_j (v_j + b_v) = sum_j p_j v_j + b_v, which the output projection turns
+ * into a constant):
+ *   bias_out[n] = bias_in[n] - (n >= D ? bqkv[n] : 0)          n < 3D
+ *   bproj_out[j] = bproj[j] + sum_c wproj[j][c] * bqkv[2D + c]   j < D
+ * bias_in: the bias the contraction would use (bqkv itself, or the bias_f of
+ * ssam_fold_ln_weight); wproj dev bf16 [D][D] row-major (not packed); all other
+ * arguments dev fp32.  The rows of LN1-zero padding tokens then have k = v = 0. */
+int ssam_fold_kv_bias(const float *bias_in, const float *bqkv, const void *wproj, const float *bproj,
+                      float *bias_out, float *bproj_out, int D, void *stream);
 int ssam_linear_ln(const void *x, int ldx, const float *stats, const void *Wfp, const float *colsum,
                    const float *bias_f, void *C, int ldc, int M, int N, int K,
                    const int32_t *row_map, int rows_per_batch, int map_batch_stride, int dst_rows_per_batch,
@@ -293,6 +305,11 @@ typedef struct ssam_block_weights {     /* every pointer: dev */
                                            SSAM_EUNSUPPORTED. */
     const float *qkv_colsum;            /* [3D] fp32 (fold_ln1 only)                 */
     const float *bqkv_folded;           /* [3D] fp32 (fold_ln1 only)                 */
+    int fold_kv_bias;                   /* != 0 (needs fold_ln1 != 0): bqkv_folded and bproj_folded are the outputs
+                                           of ssam_fold_kv_bias; the padding slots of a window then hold zero keys
+                                           and values for every block, so a stack writes them once instead of once
+                                           per block. */
+    const float *bproj_folded;          /* [D] fp32 (fold_kv_bias only)              */
 } ssam_block_weights;
 
 typedef struct ssam_block_cfg {

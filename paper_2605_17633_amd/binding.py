@@ -33,7 +33,8 @@ _WEIGHT_POINTERS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj",
 
 class BlockWeights(C.Structure):
     _fields_ = ([(n, C.c_void_p) for n in _WEIGHT_POINTERS] + [("packed", C.c_int), ("fold_ln1", C.c_int),
-                ("qkv_colsum", C.c_void_p), ("bqkv_folded", C.c_void_p)])
+                ("qkv_colsum", C.c_void_p), ("bqkv_folded", C.c_void_p), ("fold_kv_bias", C.c_int),
+                ("bproj_folded", C.c_void_p)])
 
 
 class BlockCfg(C.Structure):
@@ -336,9 +337,22 @@ def ssam_linear_ln(x, stats, Wfp, colsum, bias_f, out, row_map, rows_per_batch, 
     return out
 
 
-def pack_block_weights(wt: dict, fold_ln1=False) -> dict:
-    """Device weight dict -> the same with the four Linear weights in fragment order (flagged 'packed').
-    fold_ln1: wqkv becomes the packed LN1-folded weight (ssam_fold_ln_weight), with its column sums and bias."""
+def ssam_fold_kv_bias(bias_in, bqkv, wproj, bproj):
+    """-> (bias_out [3D], bproj_out [D]) fp32, see the header; wproj row-major."""
+    D = bproj.numel()
+    _dev(wproj, torch.bfloat16, "wproj")
+    bias_out = torch.empty(3 * D, dtype=torch.float32, device=bproj.device)
+    bproj_out = torch.empty(D, dtype=torch.float32, device=bproj.device)
+    _check("ssam_fold_kv_bias", lib().ssam_fold_kv_bias(
+        _f32(bias_in, "bias_in"), _f32(bqkv, "bqkv"), _bf(wproj, "wproj"), _f32(bproj, "bproj"), _f32(bias_out, "bias_out"),
+        _f32(bproj_out, "bproj_out"), C.c_int(D), _stream()))
+    return bias_out, bproj_out
+
+
+def pack_block_weights(wt: dict, fold_ln1=False, fold_kv_bias=False) -> dict:
+    """Device weight dict (row-major weights) -> the same with the four Linear weights in fragment order (flagged
+    'packed').  fold_ln1: wqkv becomes the packed LN1-folded weight (ssam_fold_ln_weight), with its column sums
+    and bias; fold_kv_bias (with fold_ln1): the key and value biases move out of the contraction (ssam_fold_kv_bias)."""
     out = dict(wt)
     for k in _PACKABLE:
         out[k] = ssam_pack_weight(wt[k])
@@ -347,16 +361,21 @@ def pack_block_weights(wt: dict, fold_ln1=False) -> dict:
         Wf, colsum, bias_f = ssam_fold_ln_weight(wt["wqkv"], wt["bqkv"], wt["ln1_g"], wt["ln1_b"])
         out["wqkv"] = ssam_pack_weight(Wf)
         out["qkv_colsum"], out["bqkv_folded"], out["fold_ln1"] = colsum, bias_f, True
+        if fold_kv_bias:
+            out["bqkv_folded"], out["bproj_folded"] = ssam_fold_kv_bias(bias_f, wt["bqkv"], wt["wproj"], wt["bproj"])
+            out["fold_kv_bias"] = True
+    elif fold_kv_bias:
+        raise ValueError("fold_kv_bias needs fold_ln1")
     return out
 
 
-def upload_block_weights(wdict: dict, device="cuda", pack=False, fold_ln1=False) -> dict:
+def upload_block_weights(wdict: dict, device="cuda", pack=False, fold_ln1=False, fold_kv_bias=False) -> dict:
     """numpy fp32 dict (bf16-representable values) -> device tensors in the ABI's dtypes."""
     out = {}
     for k, v in wdict.items():
         t = torch.from_numpy(np.ascontiguousarray(v))
         out[k] = t.to(device=device, dtype=torch.bfloat16 if k in _BF16_FIELDS else torch.float32).contiguous()
-    return pack_block_weights(out, fold_ln1=fold_ln1) if pack else out
+    return pack_block_weights(out, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias) if pack else out
 
 
 def block_weights_struct(wt: dict) -> BlockWeights:
@@ -372,6 +391,10 @@ def block_weights_struct(wt: dict) -> BlockWeights:
         for name in ("qkv_colsum", "bqkv_folded"):
             _dev(wt[name], torch.float32, name)
             setattr(s, name, wt[name].data_ptr())
+    s.fold_kv_bias = 1 if wt.get("fold_kv_bias") else 0
+    if s.fold_kv_bias:
+        _dev(wt["bproj_folded"], torch.float32, "bproj_folded")
+        s.bproj_folded = wt["bproj_folded"].data_ptr()
     return s
 
 

@@ -143,12 +143,17 @@ extern "C" int ssam_routed_mlp_packed(void *x, const int32_t *keep_idx, const fl
 
 // everything but the padding tables, which sit behind it (so that no step of either half overwrites them
 // and a stack of blocks can build them once)
-static size_t block_core_bytes(const ssam_block_cfg *cfg, const BlockGeom &g)
+static size_t attn_half_bytes(const ssam_block_cfg *cfg, const BlockGeom &g)
 {
     size_t rows = (size_t)cfg->B * g.Nout;
-    size_t attn = align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2) + GEMM_SPLIT_WS_BYTES;
-    size_t mlp = mlp_ws_bytes(cfg->B, cfg->K, cfg->D, cfg->Dm);
-    return attn > mlp ? attn : mlp;
+    return align256(rows * cfg->D * 2) + align256(rows * 3 * cfg->D * 2) + GEMM_SPLIT_WS_BYTES;
+}
+
+static size_t block_core_bytes(const ssam_block_cfg *cfg, const BlockGeom &g)
+{
+    // the two halves do not share memory: the padding slots of the qkv tensor can then keep their contents from
+    // block to block (see fold_kv_bias)
+    return attn_half_bytes(cfg, g) + mlp_ws_bytes(cfg->B, cfg->K, cfg->D, cfg->Dm);
 }
 
 extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
@@ -162,7 +167,7 @@ extern "C" size_t ssam_encoder_block_workspace_bytes(const ssam_block_cfg *cfg)
 static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
                               const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
                               void *workspace, size_t workspace_bytes, void **qkv_events, unsigned char *tables,
-                              bool tables_ready, void *stream)
+                              bool tables_ready, bool *pad_rows_zero, void *stream)
 {
     BlockGeom g;
     if (!x || !w || !gather_table || !sigma || !keep_idx || !workspace || !block_geom(cfg, g)) return SSAM_EINVAL;
@@ -188,10 +193,13 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     GemmRowMap none = { nullptr, 1, 0, 1 };
     int rc;
     const bool fold = w->fold_ln1 != 0;
+    const bool kv_shift = w->fold_kv_bias != 0;
     if (fold) {
         if (!packed || !w->qkv_colsum || !w->bqkv_folded) return SSAM_EINVAL;
         if (crows % 128 != 0 || (3 * D) % 256 != 0) return SSAM_EUNSUPPORTED;
     }
+    if (kv_shift && (!fold || !w->bproj_folded)) return SSAM_EINVAL;
+    const float *bproj = kv_shift ? w->bproj_folded : w->bproj;
     if (!tables_ready) {
         rc = build_block_tables(cfg, g, gather_table, tables, st);
         if (rc != SSAM_OK) return rc;
@@ -210,6 +218,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
     }
 
     if (!padded) {
+        if (pad_rows_zero) *pad_rows_zero = false;              // this block's qkv tensor lies over the windowed blocks' one
         if (!fold) {
             rc = ssam_ln_gather(x, gather_table, per_image ? g.Nout : 0, w->ln1_g, w->ln1_b, cfg->eps, u, B, g.N, g.Nout, D, stream);
             if (rc != SSAM_OK) return rc;
@@ -223,7 +232,7 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
                                    1.0f / sqrtf((float)g.d), stream);
         if (rc != SSAM_OK) return rc;
         GemmRowMap back = { gather_table, g.Nout, per_image ? g.Nout : 0, g.N };
-        rc = ssam_linear_impl(u, w->wproj, w->bproj, x, rows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        rc = ssam_linear_impl(u, w->wproj, bproj, x, rows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
         if (rc != SSAM_OK) return rc;
     } else {
         // Windows with padding: the padding slots are zero rows after LN1, so their qkv rows are the bias and
@@ -240,26 +249,37 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
             rc = ssam_linear_impl(u, w->wqkv, w->bqkv, qkv, crows, 3 * D, D, GemmLd{ D, D, 3 * D }, packed, SSAM_EPI_BIAS_SCATTER, to_slot, 0, split, GEMM_SPLIT_WS_BYTES, st);
             if (rc != SSAM_OK) return rc;
         }
-        rc = ssam_fill_bias_rows(qkv, 3L * D, w->bqkv, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
-        if (rc != SSAM_OK) return rc;
+        // the padding slots hold the qkv of a zero row: the bias, or, with the key and value biases taken out of
+        // the contraction, zeros in the columns attention reads (k, v), which then need writing only when something
+        // else has used the memory since
+        if (!kv_shift) {
+            rc = ssam_fill_bias_rows(qkv, 3L * D, w->bqkv, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
+            if (rc != SSAM_OK) return rc;
+            if (pad_rows_zero) *pad_rows_zero = false;
+        } else if (!pad_rows_zero || !*pad_rows_zero) {
+            rc = ssam_fill_bias_rows(qkv, 3L * D, nullptr, 3 * D, pt.pad_slot, g.Nout - g.N, g.Nout, B, st);
+            if (rc != SSAM_OK) return rc;
+            if (pad_rows_zero) *pad_rows_zero = true;
+        }
         if (qkv_events && qkv_events[1] && hipEventRecord((hipEvent_t)qkv_events[1], st) != hipSuccess) return SSAM_EHIP;
         rc = ssam_sparse_attention(qp, qp + D, qp + 2 * D, 3L * D, w->rel_h, w->rel_w, sigma, per_image ? g.S : 0, u, pt.slot_row,
                                    B * g.nW, g.S, g.w, cfg->heads, g.d, cfg->mask_block, cfg->r,
                                    1.0f / sqrtf((float)g.d), stream);
         if (rc != SSAM_OK) return rc;
         GemmRowMap back = { pt.real_spatial, g.N, g.N, g.N };
-        rc = ssam_linear_impl(u, w->wproj, w->bproj, x, crows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
+        rc = ssam_linear_impl(u, w->wproj, bproj, x, crows, D, D, GemmLd{ D, D, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, back, 0, split, GEMM_SPLIT_WS_BYTES, st);
         if (rc != SSAM_OK) return rc;
     }
+    const size_t attn_bytes = attn_half_bytes(cfg, g);
     return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, packed,
-                           B, g.N, D, cfg->Dm, cfg->K, workspace, workspace_bytes, stream);
+                           B, g.N, D, cfg->Dm, cfg->K, ws + attn_bytes, mlp_ws_bytes(B, cfg->K, D, cfg->Dm), stream);
 }
 
 extern "C" int ssam_encoder_block(void *x, const ssam_block_weights *w, const ssam_block_cfg *cfg,
                                   const int32_t *gather_table, const int32_t *sigma, const int32_t *keep_idx,
                                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, nullptr, false, stream);
+    return encoder_block_impl(x, w, cfg, gather_table, sigma, keep_idx, workspace, workspace_bytes, nullptr, nullptr, false, nullptr, stream);
 }
 
 extern "C" size_t ssam_encoder_workspace_bytes(const ssam_block_cfg *cfg_local, const ssam_block_cfg *cfg_global)
@@ -337,11 +357,12 @@ extern "C" int ssam_encoder_forward(void *x, const ssam_block_weights *weights, 
         rc = build_block_tables(cfg_global, gg, global_table, tables_global, (hipStream_t)stream);
         if (rc != SSAM_OK) return rc;
     }
+    bool pad_rows_zero = false;                 // the padding slots of the windowed blocks' qkv tensor hold zeros
     for (int i = 0; i < n_blocks; ++i) {
         void **ev = qkv_events ? qkv_events + 2 * i : nullptr;
         rc = is_global[i]
-                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, core, ev, tables_global, true, stream)
-                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, core, ev, tables_local, true, stream);
+                 ? encoder_block_impl(x, &weights[i], cfg_global, global_table, sigma_global, keep_idx, workspace, core, ev, tables_global, true, &pad_rows_zero, stream)
+                 : encoder_block_impl(x, &weights[i], cfg_local, window_table, sigma_window, keep_idx, workspace, core, ev, tables_local, true, &pad_rows_zero, stream);
         if (rc != SSAM_OK) return rc;
     }
     return SSAM_OK;

@@ -189,6 +189,30 @@ fold_ln_weight_kernel(const bf16 *__restrict__ W, int ldw, const float *__restri
     if (lane == 0) { colsum[n] = cs; bias_f[n] = bias[n] + bs; }
 }
 
+// Key and value biases taken out of the qkv contraction (softmax over keys does not see a term that is the same
+// for every key, and the probabilities of a query sum to one): one wave per output channel.
+//   bias_out[n] = bias_in[n] - (n >= D ? bqkv[n] : 0)   n < 3D;   bproj_out[j] = bproj[j] + sum_c wproj[j][c] bqkv[2D + c]
+__global__ void __launch_bounds__(256)
+fold_kv_bias_kernel(const float *__restrict__ bias_in, const float *__restrict__ bqkv, const bf16 *__restrict__ wproj,
+                    const float *__restrict__ bproj, float *__restrict__ bias_out, float *__restrict__ bproj_out, int D)
+{
+    int lane = threadIdx.x & 63;
+    int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (n >= 3 * D) return;
+    if (lane == 0) bias_out[n] = bias_in[n] - (n >= D ? bqkv[n] : 0.f);
+    if (n < D) {
+        float acc = 0.f;
+        for (int c = lane; c < D / 8; c += 64) {
+            float w[8];
+            unpack_bf16x8(*reinterpret_cast<const uint4 *>(wproj + (long)n * D + c * 8), w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += w[e] * bqkv[2 * D + c * 8 + e];
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) bproj_out[n] = bproj[n] + acc;
+    }
+}
+
 // inv[b][table[b][p]] = p for every slot p that holds a token (table entries < 0 are padding)
 __global__ void __launch_bounds__(256)
 invert_table_kernel(const int32_t *__restrict__ table, int table_batch_stride, int Nout, int N, int32_t *__restrict__ inv, int total)
@@ -384,7 +408,7 @@ compact_slots_kernel(const int32_t *__restrict__ table, int table_batch_stride, 
     }
 }
 
-// rows[b*rows_per_batch + pad_slot[b][i]] = bf16(bias): one wave per row, 16 bytes per lane
+// rows[b*rows_per_batch + pad_slot[b][i]] = bf16(bias) (bias == nullptr: zeros): one wave per row, 16 bytes per lane
 __global__ void __launch_bounds__(256)
 fill_bias_rows_kernel(bf16 *__restrict__ C, long ldc, const float *__restrict__ bias, int n_cols,
                       const int32_t *__restrict__ pad_slot, int npad, int rows_per_batch, int total_rows)
@@ -394,6 +418,10 @@ fill_bias_rows_kernel(bf16 *__restrict__ C, long ldc, const float *__restrict__ 
     const int b = r / npad, i = r - b * npad;
     bf16 *dst = C + ((long)b * rows_per_batch + pad_slot[(long)b * npad + i]) * ldc;
     for (int c = lane * 8; c < n_cols; c += 64 * 8) {
+        if (bias == nullptr) {
+            *reinterpret_cast<uint4 *>(dst + c) = make_uint4(0, 0, 0, 0);
+            continue;
+        }
         const float4 *b4 = reinterpret_cast<const float4 *>(bias + c);
         float4 x0 = b4[0], x1 = b4[1];
         float v[8] = { x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w };
@@ -603,6 +631,18 @@ int ssam_invert_table(const int32_t *table, int table_batch_stride, int B, int N
 {
     const int total = B * Nout;
     hipLaunchKernelGGL(invert_table_kernel, dim3(ssam_div_up(total, 256)), dim3(256), 0, st, table, table_batch_stride, Nout, N, inv, total);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
+extern "C" int ssam_fold_kv_bias(const float *bias_in, const float *bqkv, const void *wproj, const float *bproj,
+                                 float *bias_out, float *bproj_out, int D, void *stream)
+{
+    if (!bias_in || !bqkv || !wproj || !bproj || !bias_out || !bproj_out || D <= 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(wproj)) return SSAM_EINVAL;
+    if (D % 8 != 0) return SSAM_EUNSUPPORTED;
+    hipLaunchKernelGGL(fold_kv_bias_kernel, dim3(ssam_div_up(3 * D, 4)), dim3(256), 0, (hipStream_t)stream,
+                       bias_in, bqkv, (const bf16 *)wproj, bproj, bias_out, bproj_out, D);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }

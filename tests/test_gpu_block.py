@@ -173,10 +173,10 @@ def make_block_case(seed, B_, g, shape, ws, rho, scale_w=1.0):
     return wt, x, keep, K
 
 
-def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4, fold_ln1=False):
+def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4, fold_ln1=False, fold_kv_bias=False):
     B_, g = x.shape[0], x.shape[1]
     n = g * g
-    wd = B.upload_block_weights(wt, pack=fold_ln1, fold_ln1=fold_ln1)
+    wd = B.upload_block_weights(wt, pack=fold_ln1, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias)
     cfg = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, ws, Bm, keep.shape[1], r)
     if ws > 0:
         table = dev_i32(oracle.window_table(g, ws, G))
@@ -228,11 +228,16 @@ def test_encoder_block_folded_ln1(name, ws, Bm, shape_name):
     rng = np.random.default_rng(34)
     wt["ln1_g"] = (1.0 + 0.3 * rng.normal(size=shape.D)).astype(np.float32)
     wt["ln1_b"] = (0.2 * rng.normal(size=shape.D)).astype(np.float32)
-    got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4, fold_ln1=True)
+    # biases large enough that a dropped or misplaced one shows
+    for kname, scale in (("bqkv", 0.5), ("bproj", 0.2)):
+        wt[kname] = (scale * rng.normal(size=wt[kname].shape)).astype(np.float32)
     ow = oracle.BlockWeights(**wt)
-    for b in range(x.shape[0]):
-        ref = oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, 0.4, keep[b])
-        assert_close(got[b] - x[b], ref - x[b], f"folded LN1, {name}: block delta b={b}", stored=ref, updates=2)
+    refs = [oracle.encoder_block(x[b], ow, shape.heads, ws, 4, Bm, 0.4, keep[b]) for b in range(x.shape[0])]
+    for kv in (False, True):        # kv: key and value biases taken out of the contraction as well
+        got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4, fold_ln1=True, fold_kv_bias=kv)
+        for b in range(x.shape[0]):
+            assert_close(got[b] - x[b], refs[b] - x[b], f"folded LN1 (kv bias moved: {kv}), {name}: block delta b={b}",
+                         stored=refs[b], updates=2)
 
 
 def test_encoder_block_folded_ln1_unsupported():

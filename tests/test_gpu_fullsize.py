@@ -57,7 +57,7 @@ def test_vit_h_block_full_size(ws, Bm, img):
     assert_close(got - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} image {img}", stored=ref, updates=2)
     # the same block with packed weights and LN1 folded into the qkv contraction (the form bench.py times)
     xf = torch.from_numpy(x.reshape(BATCH, n, SHAPE.D)).to(DEV).to(torch.bfloat16).contiguous()
-    wf = B.pack_block_weights(wd, fold_ln1=True)
+    wf = B.pack_block_weights(wd, fold_ln1=True, fold_kv_bias=True)
     B.ssam_encoder_block(xf, B.block_weights_struct(wf), cfg, table, sigma, keep)
     torch.cuda.synchronize()
     gotf = to_np(xf[img]).reshape(G, G, SHAPE.D)
@@ -91,7 +91,7 @@ def test_vit_h_encoder_full_depth():
     ws_buf = torch.empty(B.ssam_encoder_workspace_bytes(cfg_l, cfg_g), dtype=torch.uint8, device=DEV)
     # the run that is compared with the oracle has the Linear weights in MFMA fragment order and LN1 folded into
     # the qkv contraction (the form bench.py times)
-    wps = [B.pack_block_weights(w, fold_ln1=True) for w in wds]      # kept alive: the structs hold raw pointers
+    wps = [B.pack_block_weights(w, fold_ln1=True, fold_kv_bias=True) for w in wds]      # kept alive: the structs hold raw pointers
     packed = [B.block_weights_struct(w) for w in wps]
     B.ssam_encoder_forward(xd, packed, flags, cfg_l, cfg_g, wtab, wsig, gtab, gtab, scores, keep, ws_buf)
     torch.cuda.synchronize()
