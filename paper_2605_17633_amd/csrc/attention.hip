@@ -61,7 +61,22 @@ struct AttnCfg {
     static constexpr int DT = (D + 31) / 32;     // 32-row tiles of O^T
     static constexpr int KSTR = D + 8;           // row stride in LDS (elements): odd in 16-byte units
     static constexpr int CH = D / 8;             // 16-byte chunks per row
+    // D = 16 mod 32: the last 32-row tile of O^T has 16 rows to spare and the LDS rows of V have 8 columns of
+    // padding; with ones in that padding those rows come out of the P V product as the sum of the probabilities,
+    // which the softmax then does not have to add up on the vector unit
+    static constexpr bool ONES = D % 32 == 16;
 };
+
+// fill the padding columns of `rows` LDS rows of V with 1.0 (they are never written afterwards: tile stores cover
+// the D real columns only)
+template <int D>
+__device__ __forceinline__ void set_ones_columns(bf16 *Vs, int rows, int tid, int nthreads)
+{
+    if constexpr (AttnCfg<D>::ONES) {
+        const u32x4 ones = { 0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u };
+        for (int p = tid; p < rows; p += nthreads) *reinterpret_cast<u32x4 *>(Vs + p * AttnCfg<D>::KSTR + D) = ones;
+    }
+}
 
 // Per-wave softmax/output state for 32 queries (one per lane pair l, l^32).
 template <int D>
@@ -254,7 +269,7 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
         const float mnew = move ? mx : st.m;
         const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
         st.m = mnew;
-        st.l *= alpha;
+        if constexpr (!C::ONES) st.l *= alpha;
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -268,11 +283,11 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 s[b][r] = __builtin_amdgcn_exp2f(s[b][r] - mref);
-                psum += s[b][r];
+                if constexpr (!C::ONES) psum += s[b][r];
             }
         }
     }
-    st.l += psum;
+    if constexpr (!C::ONES) st.l += psum;
     // transposing read: lane li of a 16-lane group points at row (li >> 2), column chunk (li & 3) of a
     // 4-key x 16-feature block and receives the 4 keys of feature column li
     const int li = lane & 15, fblk = (lane >> 4) & 1;
@@ -288,7 +303,10 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
 #pragma unroll
                 for (int dt = 0; dt < C::DT; ++dt) {
                     int col = dt * 32 + 16 * fblk + 4 * (li & 3);
-                    col = col <= D - 4 ? col : D - 4;    // feature columns past D re-read the last ones; outputs dropped
+                    // feature columns past D re-read the last ones and their outputs are dropped; with ONES they are
+                    // the ones columns D .. D+7, and their outputs are the sums of the probabilities
+                    constexpr int CMAX = C::ONES ? D + 4 : D - 4;
+                    col = col <= CMAX ? col : CMAX;
                     const bf16 *v0p = vblk + 16 * t * C::KSTR + col;
                     bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p));
                     bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p + 8 * C::KSTR));
@@ -338,7 +356,8 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    const float l = st.l + __shfl_xor(st.l, 32, 64);
+    // ONES: row 16 + 4*half of the last tile of O^T is a ones column's output: the whole sum, in both half-waves
+    const float l = C::ONES ? st.o[C::DT - 1][8] : st.l + __shfl_xor(st.l, 32, 64);
     const float inv = 1.0f / l;
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
@@ -453,6 +472,7 @@ attn_window_kernel(AttnParams P, int n_groups)
         if (row < nrel) v = *reinterpret_cast<const u32x4 *>((tab ? P.rel_w : P.rel_h) + (long)row * D + c * 8);
         *reinterpret_cast<u32x4 *>((tab ? Rw : Rh) + row * C::KSTR + c * 8) = v;
     }
+    set_ones_columns<D>(Vs, SP, tid, (int)blockDim.x);
     const int q0 = wave * 32, qpos = q0 + l32;
     const int qclamp = qpos < S ? qpos : S - 1;
     uint32_t qrc = key_row_col(P.sigma, qclamp, S, P.w);
@@ -632,6 +652,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
     }
 
     ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt, 3)       // in flight while the bias rows are formed
+    set_ones_columns<D>(Vs, GLB_TILE, tid, 256);
     build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
 
     WaveState<D> st;
