@@ -442,3 +442,22 @@ def test_ln_fold_pieces():
         rows = np.arange(8, 512)
         assert_close(got[b * 512 + rmap[rows]], ref[b * 512 + rows], f"folded linear image {b}")
         assert np.all(got[b * 512 + np.arange(512 - 8, 512)] == 7.0)          # skipped rows' destinations untouched
+
+
+def test_fold_kv_bias():
+    """ssam_fold_kv_bias against its definition in fp64."""
+    announce("fold kv bias")
+    rng = np.random.default_rng(71)
+    D = 768
+    bias_in = rng.normal(size=3 * D).astype(np.float32)
+    bqkv = (0.5 * rng.normal(size=3 * D)).astype(np.float32)
+    wproj = inputs.bf16_round((0.02 * rng.normal(size=(D, D))).astype(np.float32))
+    bproj = (0.2 * rng.normal(size=D)).astype(np.float32)
+    to_dev = lambda a: torch.from_numpy(a).to(DEV)
+    bias_out, bproj_out = B.ssam_fold_kv_bias(to_dev(bias_in), to_dev(bqkv), dev_bf16(wproj), to_dev(bproj))
+    ref_bias = bias_in.astype(np.float64).copy()
+    ref_bias[D:] -= bqkv[D:]
+    np.testing.assert_allclose(bias_out.cpu().numpy(), ref_bias, rtol=1e-6, atol=1e-6)       # the query part is untouched
+    assert np.array_equal(bias_out.cpu().numpy()[:D], bias_in[:D])
+    ref_proj = bproj + wproj.astype(np.float64) @ bqkv[2 * D:].astype(np.float64)
+    np.testing.assert_allclose(bproj_out.cpu().numpy(), ref_proj, rtol=1e-5, atol=1e-5)
