@@ -239,6 +239,9 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         GEMM_STORE_LDS_A(0)
         GEMM_LOAD_GLOBAL_A(min(kb + 1, ke - 1))
         LDS_BARRIER();
+        // a wave in its main loop goes before the waves of the CU's other workgroup when that one is in its
+        // prologue or epilogue (priority 0): their memory instructions then fill the gaps instead of delaying MFMAs
+        __builtin_amdgcn_s_setprio(1);
         for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
             GEMM_LOAD_AFRAGS(buf, 0, 0)
             GEMM_LOAD_AFRAGS(buf, 1, 1)
@@ -273,6 +276,7 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         GEMM_LOAD_AFRAGS(buf, 3, 1)
         GEMM_MFMAS_W(0, 2)
         GEMM_MFMAS_W(1, 3)
+        __builtin_amdgcn_s_setprio(0);
     } else {
     GEMM_LOAD_GLOBAL(kb)
     GEMM_STORE_LDS(0)
