@@ -665,6 +665,8 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
         const int kt_next = a + 1 < P.n_pre ? a + 1 : qt;
         if (a + 1 < nact) ATTN_LOAD_TILE(kt_next, NB < GLB_TILE / 32 ? 1 : 3)     // one step per tile: nothing to put V between
         const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
+        // the softmax / MFMA phase goes ahead of the other workgroup's tile traffic (loads, LDS stores, barriers)
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int c0 = 0; c0 < GLB_TILE / 32; c0 += NB) {
             if (c0 >= nblk) break;
@@ -679,6 +681,7 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
                 attn_chunk_step<D, NB, false, false, GlbTab, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
             if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
         }
+        __builtin_amdgcn_s_setprio(0);
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
 }
