@@ -32,8 +32,9 @@
 // Two launch shapes:
 //   window kernel: persistent workgroups looping over (window, head) problems, one
 //                  wave per 32-query tile (= mask tile of 32), the window's whole K
-//                  and V in LDS, the next problem's K, V, Q prefetched into registers
-//                  in three pieces, the rel-pos tables resident in LDS;
+//                  and V in LDS, the next problem's K and V prefetched into registers
+//                  and its Q straight into LDS, in three pieces, the rel-pos tables
+//                  resident in LDS;
 //   global kernel: one workgroup per (128-query mask tile, image, head), 4 waves, two
 //                  workgroups per CU, active 128-key tiles streamed through LDS with
 //                  register prefetch (K and V requested at different points).
@@ -342,14 +343,14 @@ __device__ __forceinline__ void load_q_frags(bf16x8 *qf, const bf16 *qrow)
 }
 
 // Normalise the wave's 32 x D output tile and write it out.  The accumulators hold O^T (lane = query,
-// registers = 4-feature groups); the tile goes through a per-wave LDS staging area ([32][KSTR] bf16) so
+// registers = 4-feature groups); the tile goes through a per-wave LDS staging area ([32][STR] bf16) so
 // that the global stores are 16 bytes per lane and cover whole rows.  `stage` may overlay LDS that only
 // this wave used (its bias rows).  out_head: the output tensor at this head's columns; my_row: the output
 // row of this lane's query (l & 31), negative = not stored (past S, or dropped by the row map).
-template <int D>
+template <int D, int STR = AttnCfg<D>::KSTR>
 __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, bf16 *out_head, long out_stride, long my_row)
 {
-    using C = AttnCfg<D>;
+    using C = AttnCfg<D>;        // STR: row stride of the staging area in elements
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     // the last P V MFMAs may still be in flight and this point is reached through loop-exit branches:
     // wait their passes out explicitly before the accumulators are read (see the GEMM epilogue)
@@ -368,7 +369,7 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
                 uint2 pk;
                 pk.x = pack_bf16x2(st.o[dt][4 * g + 0] * inv, st.o[dt][4 * g + 1] * inv);
                 pk.y = pack_bf16x2(st.o[dt][4 * g + 2] * inv, st.o[dt][4 * g + 3] * inv);
-                *reinterpret_cast<uint2 *>(stage + l32 * C::KSTR + dd) = pk;
+                *reinterpret_cast<uint2 *>(stage + l32 * STR + dd) = pk;
             }
         }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // LDS is in order per wave; keep the compiler from reordering
@@ -381,7 +382,7 @@ __device__ __forceinline__ void finish_and_store(WaveState<D> &st, bf16 *stage, 
         row = row < 32 ? row : 31;
         const long orow = ((long)__shfl(row_hi, row, 64) << 32) | (unsigned)__shfl(row_lo, row, 64);   // lane `row` holds query `row`
         if (id < 32 * C::CH && orow >= 0) {
-            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * C::KSTR + c * 8);
+            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * STR + c * 8);
             *reinterpret_cast<u32x4 *>(out_head + orow * out_stride + c * 8) = v;
         }
     }
@@ -424,10 +425,25 @@ __host__ __device__ inline int wave_scratch_bytes(int ts, int esz = 4)
 // ------------------------------------------------------------------ window kernel
 inline int window_rel_rows(int w) { return ((2 * w - 1 + 31) / 32) * 32; }
 
+// per-wave LDS landing area of the next problem's queries: the KS operand-b fragments of the wave's 32 queries
+template <int D>
+__host__ __device__ constexpr int window_q_bytes() { return AttnCfg<D>::KS * 1024; }
+
+// Row stride of the output staging tile: padded like the K and V rows (conflict-free 8-byte stores) when a
+// 7-tile window then still fits the 160 KB of LDS, else the bare D (d = 80).
+template <int D>
+__host__ __device__ constexpr int window_stage_stride()
+{
+    constexpr int KSTR = AttnCfg<D>::KSTR, bias = 2 * 32 * WIN_TSTR * (int)sizeof(WinTab), stage = 32 * KSTR * 2;
+    constexpr long total = 7L * window_q_bytes<D>() + 2L * 224 * KSTR * 2 + 2L * 32 * KSTR * 2 +
+                           7L * (bias > stage ? bias : stage) + 224 * 4;
+    return total <= 160 * 1024 ? KSTR : D;
+}
+
 template <int D>
 __host__ __device__ inline int window_scratch_bytes()
 {
-    int bias = 2 * 32 * WIN_TSTR * (int)sizeof(WinTab), stage = 32 * AttnCfg<D>::KSTR * 2;
+    int bias = 2 * 32 * WIN_TSTR * (int)sizeof(WinTab), stage = 32 * window_stage_stride<D>() * 2;
     return ((bias > stage ? bias : stage) + 15) & ~15;
 }
 
@@ -435,8 +451,8 @@ template <int D>
 size_t window_lds_bytes(int nqb, int w)
 {
     int SP = nqb * 32;
-    return (size_t)2 * SP * AttnCfg<D>::KSTR * 2 + (size_t)2 * window_rel_rows(w) * AttnCfg<D>::KSTR * 2 +
-           (size_t)nqb * window_scratch_bytes<D>() + (size_t)SP * 4;
+    return (size_t)nqb * window_q_bytes<D>() + (size_t)2 * SP * AttnCfg<D>::KSTR * 2 +
+           (size_t)2 * window_rel_rows(w) * AttnCfg<D>::KSTR * 2 + (size_t)nqb * window_scratch_bytes<D>() + (size_t)SP * 4;
 }
 
 constexpr int WIN_NB = 1;            // key blocks per softmax chunk in the window kernel: one (with two the kernel has no
@@ -451,7 +467,8 @@ attn_window_kernel(AttnParams P, int n_groups)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int nqb = blockDim.x >> 6, SP = nqb * 32;
     const int nrel = 2 * P.w - 1, rrows = ((nrel + 31) / 32) * 32;      // nrel <= 32 (checked on the host)
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem);
+    bf16 *Qs = reinterpret_cast<bf16 *>(smem);    // [nqb][KS][64 lanes][8]: query fragments, one problem ahead (first in LDS)
+    bf16 *Ks = Qs + nqb * (window_q_bytes<D>() / 2);
     bf16 *Vs = Ks + SP * C::KSTR;
     bf16 *Rh = Vs + SP * C::KSTR;                 // rel-pos tables, zero-padded to rrows rows
     bf16 *Rw = Rh + rrows * C::KSTR;
@@ -480,10 +497,13 @@ attn_window_kernel(AttnParams P, int n_groups)
     const int nact = P.n_pre + (wave >= P.n_pre ? 1 : 0);
 
     u32x4 rk[WIN_MAX_LOADS], rv[WIN_MAX_LOADS];
-    bf16x8 qf[C::KS], qnext[C::KS];
+    bf16x8 qf[C::KS];
     int32_t row_next = -1;
+    bf16 *q_mine = Qs + wave * (window_q_bytes<D>() / 2) + lane * 8;        // this lane's slot in fragment 0
+    const uint32_t q_lds = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(size_t)(__attribute__((address_space(3))) bf16 *)(Qs + wave * (window_q_bytes<D>() / 2)));
 
-    // The next problem's operands are requested in three pieces (K, V, Q) spread over the current problem's
+    // The next problem's operands are requested in three pieces (K, V here, Q below) spread over the current problem's
     // phases: a CU keeps only so many cache-line requests in flight, and a wave that issues all of its loads
     // at once sits in the issue queue behind the other waves' loads instead of computing.
 #define WIN_PREFETCH(prob_, WHAT)                                                                       \
@@ -503,7 +523,22 @@ attn_window_kernel(AttnParams P, int n_groups)
             }                                                                                           \
         }                                                                                               \
         if (((WHAT) & 1) && P.out_rows != nullptr && qpos < S) row_next = P.out_rows[(long)g_ * S + qpos]; \
-        if ((WHAT) & 4) load_q_frags<D>(qnext, P.q + base_ + (long)qclamp * P.row_stride);              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+    // The queries of a problem do not pass through registers: 16-byte loads with an LDS destination drop fragment
+    // ks of the wave's 32 queries into its landing area (lane l's 16 bytes at 16*l, the layout operand b wants)
+    // while the problem before it is still in its chunk loop, which has no registers to spare for them.  The
+    // compiler does not see these requests; the kernel waits for them itself before it reads the landing area.
+    // The wait in front makes sure the LDS reads of the current fragments have returned.
+#define WIN_PREFETCH_Q(prob_)                                                                           \
+    {                                                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        const int g_ = (prob_) / P.h, hd_ = (prob_) % P.h;                                              \
+        const bf16 *qsrc_ = P.q + (long)g_ * S * P.row_stride + (long)hd_ * D + (long)qclamp * P.row_stride + (lane >> 5) * 8; \
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                              \
+        _Pragma("unroll") for (int ks = 0; ks < C::KS; ++ks)                                            \
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"                          \
+                         :: "s"(q_lds + ks * 1024), "v"(qsrc_ + ks * 16) : "m0", "memory");             \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
 
@@ -514,7 +549,10 @@ attn_window_kernel(AttnParams P, int n_groups)
     auto local_problem = [&](int lp) { int g = xcd + 8 * (lp / P.h); return g < n_groups ? g * P.h + lp % P.h : -1; };
     int lp = blockIdx.x >> 3;
     int prob = local_problem(lp);
-    if (prob >= 0) WIN_PREFETCH(prob, 7)
+    if (prob >= 0) {
+        WIN_PREFETCH_Q(prob)
+        WIN_PREFETCH(prob, 3)
+    }
     for (; prob >= 0; lp += nslots, prob = local_problem(lp)) {
         const int grp = prob / P.h, head = prob % P.h;
         long my_row = -1;                         // output row of this lane's query (a mapped row was requested a problem ahead)
@@ -533,8 +571,12 @@ attn_window_kernel(AttnParams P, int n_groups)
             for (int p = tid; p < SP; p += blockDim.x) krc[p] = key_bias_offsets_window(sg, p, S, P.w);
             qrc = key_row_col(sg, qclamp, S, P.w);
         }
+        // this problem's queries were sent to LDS during the previous problem (WIN_PREFETCH_Q): wait for every
+        // outstanding request of this wave (the K and V registers above have been waited for already; what else is
+        // in flight is the previous problem's output stores) before reading them
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = qnext[ks];
+        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(q_mine + ks * 512);
         const int next = local_problem(lp + nslots);
         if (next >= 0) WIN_PREFETCH(next, 1)
         build_bias_rows_window<D>(qf, Rh, Rw, C::KSTR, tq);
@@ -559,9 +601,12 @@ attn_window_kernel(AttnParams P, int n_groups)
 #pragma unroll
             for (int b = 0; b < WIN_NB; ++b) ragged |= (a0 + b < nact) && key0[b] + 32 > S;
             attn_chunk<D, WIN_NB, WinTab>(st, qf, Ks, Vs, krc, blk, key0, min(WIN_NB, nact - a0), ragged, S, P.scale_log2e, tq_h, tq_w);
+            // after the second chunk (the only one, when the tile has one): early enough to cover the request's
+            // latency with the last chunk and the output stores on the tiles that have three, and not in the same
+            // burst as the K or the V requests
+            if (a0 == (nact > WIN_NB ? WIN_NB : 0) && next >= 0) WIN_PREFETCH_Q(next)
         }
-        if (next >= 0) WIN_PREFETCH(next, 4)
-        finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
+        finish_and_store<D, window_stage_stride<D>()>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
     }
 }
 
