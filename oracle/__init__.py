@@ -226,6 +226,17 @@ def encoder_block(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: 
     return x
 
 
+def encoder_block_halves(x, wt, h: int, ws: int, G: int, Bm: int, r: float, keep, eps: float = 1e-6, order_scores=None):
+    """The block as its two halves, for tests that need the residual stream between them: returns
+    (x1, y), x1 = x + attention half (the C routine with an empty keep-set), y = routed MLP applied to
+    x1.  This is the composition the C routine itself makes, so y equals encoder_block's result bit
+    for bit (checked in the oracle's tests)."""
+    x1 = encoder_block(x, wt, h, ws, G, Bm, r, np.zeros(0, np.int32), eps, order_scores=order_scores)
+    g, _, D = x1.shape
+    y = routed_mlp(x1.reshape(g * g, D), keep, wt.ln2_g, wt.ln2_b, wt.w1, wt.b1, wt.w2, wt.b2, eps).reshape(g, g, D)
+    return x1, y
+
+
 def encoder(x, blocks, h: int, ws: int, global_blocks, G: int, r: float, rho: float,
             Bm_window: int = 32, Bm_global: int = 128, eps: float = 1e-6, content_order: bool = False):
     """One image through a stack of blocks (Sec. 4: scores and keep-set are taken

@@ -4,6 +4,7 @@ import sys
 import numpy as np
 
 TOL = 2e-2   # max relative error for bf16-compute / fp32-accumulate outputs
+ELEM_SLACK_LARGE = 1.25   # element-wise clause on tensors of 2^20 elements or more, see assert_close
 
 
 def announce(*parts):
@@ -12,32 +13,108 @@ def announce(*parts):
     sys.stdout.flush()
 
 
-def assert_close(got, ref, what, tol=TOL, stored=None, updates=1, scale=None):
-    """Floating-point parity bar.
-    Headline: max|got-ref| / max|ref| <= tol  (`scale` replaces max|ref| when `got` is a
-    sub-selection of a larger tensor).
-    Systematic error: rms(got-ref) <= tol/2 * rms(ref); catches a wrong-by-a-factor result
-    that a single large reference element could hide in the headline.
-    When `got` is an in-place update of a bf16 tensor taken as a difference (y - x), `stored`
-    is the reference value of y and `updates` the number of residual updates behind it: each
-    one rounds the bf16 stream once (half an ulp, <= 2^-9 |y|), which no kernel can avoid, so
-    updates * 2^-9 * rms(y) is allowed on top of the rms bound."""
+def bf16_half_ulp(a):
+    """Half a unit in the last place of the bf16 number nearest to |a| (8 significant bits):
+    |a| in [2^k, 2^(k+1)) -> 2^(k-8); 0 -> 0."""
+    a = np.abs(np.asarray(a, np.float64))
+    _, e = np.frexp(a)                       # |a| = m * 2^e, m in [0.5, 1)  ->  k = e - 1
+    return np.where(a > 0, np.ldexp(1.0, e - 9), 0.0)
+
+
+def assert_close(got, ref, what, tol=TOL, stored=None, updates=1, scale=None, elem_slack=None, rms_updates=None):
+    """Floating-point parity bar, three clauses, all of them asserted.
+
+    Headline:     max(|got-ref| - A) / max|ref| <= tol   (`scale` replaces max|ref| when `got` is a
+                  sub-selection of a larger tensor).
+    Element-wise: |got-ref| - A <= elem_slack * (tol*|ref| + tol*rms(ref)) for EVERY element.
+    Systematic:   rms(got-ref) <= tol/2 * rms(ref) [+ updates * 2^-9 * rms(stored)]; catches a
+                  wrong-by-a-factor result that single large reference elements could hide
+                  (`rms_updates` replaces `updates` here for a result with bf16 intermediates inside).
+
+    A is zero unless `got` is an in-place update of a bf16 tensor taken as a difference (y - x): then
+    `stored` names the reference values the stream held (an array, or a tuple such as (x, x1, y): the
+    element-wise largest magnitude is taken) and `updates` how many times it was stored.  Each store
+    rounds the bf16 stream once, by up to half an ulp of the stored value, 2^(floor(log2|y|) - 8), i.e.
+    between 2^-9 |y| and 2^-8 |y| (bf16 has 8 significant bits).  No kernel can avoid that and the fp64
+    reference does not have it; A = updates * half_ulp_bf16(stored) is exactly that much, so the
+    headline and element-wise clauses bound the kernels' own error.  (A result computed exactly and
+    stored through the bf16 stream already shows 0.7e-2 .. 2.1e-2 of max|y - x| on these tests.)
+
+    elem_slack: 1.0 for tensors under 2^20 elements and 1.25 from there on (ELEM_SLACK_LARGE), unless a
+    test names its own, which it does only for a case listed with its measured margin and the reason in
+    the design notes.  Why the size matters: the kernels' own error is Gaussian to a good approximation,
+    sigma = 4e-3 .. 5e-3 rms(ref) for a block update, so tol * rms(ref) is a cut at 4 to 5 sigma, and the
+    largest of N such errors grows as sigma * sqrt(2 ln N): 5.3 sigma at 10^6 elements, 5.6 sigma at the
+    5.2 * 10^6 of one ViT-H image.  Measured worst ratios at full size: 0.79 .. 1.05."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{what}: non-finite values in the GPU result"
+    if elem_slack is None:
+        elem_slack = ELEM_SLACK_LARGE if got.size >= 2 ** 20 else 1.0
     scale = np.abs(ref).max() if scale is None else scale
     rms = np.sqrt(np.mean(ref ** 2))
     err = np.abs(got - ref)
-    headline = err.max() / max(scale, 1e-30)
     rms_err = np.sqrt(np.mean(err ** 2))
     rms_bound = 0.5 * tol * rms
+    own = err
     if stored is not None:
-        rms_bound += updates * 2.0 ** -9 * np.sqrt(np.mean(np.asarray(stored, np.float64) ** 2))
-    print(f"[parity] {what}: max_rel={headline:.3e} rms_err/rms_ref={rms_err / max(rms, 1e-30):.3e}", flush=True)
+        parts = stored if isinstance(stored, (tuple, list)) else (stored,)
+        st = np.maximum.reduce([np.abs(np.asarray(p, np.float64)) for p in parts])
+        rms_bound += (updates if rms_updates is None else rms_updates) * 2.0 ** -9 * np.sqrt(np.mean(st ** 2))
+        own = np.maximum(err - updates * bf16_half_ulp(st), 0.0)
+    headline = own.max() / max(scale, 1e-30)
+    worst = float((own / (tol * np.abs(ref) + tol * rms + 1e-300)).max())
+    print(f"[parity] {what}: max_rel={headline:.3e} rms_err/rms_ref={rms_err / max(rms, 1e-30):.3e} "
+          f"elementwise(err/bound)={worst:.3f}", flush=True)
     assert headline <= tol, f"{what}: max relative error {headline:.3e} > {tol}"
+    assert worst <= elem_slack, f"{what}: element-wise bound exceeded by a factor {worst:.3f} (allowed {elem_slack})"
     assert rms_err <= rms_bound, f"{what}: rms error {rms_err:.3e} > {rms_bound:.3e}"
     return headline
+
+
+DRIFT_MAX, DRIFT_RMS = 5e-2, 2.5e-2
+
+
+def assert_drift(got, ref, x0, what, depth):
+    """Drift report of a free-running stack of `depth` blocks: NOT the parity bar (that one is held per
+    block, teacher-forced, by assert_close).  got, ref: output tensors; x0: the stack's input.
+    The bf16 residual stream is rounded in place 2*depth times, each rounding uniform within 2^-9 |y|;
+    they add as a random walk that the fp64 oracle does not have, and every block's own error is carried
+    through the later blocks.  Bar: max|got-ref| <= 5e-2 * max|ref-x0| and
+    rms(got-ref) <= 2.5e-2 * rms(ref-x0) + sqrt(2*depth) * 2^-9 * rms(ref)."""
+    got, ref, x0 = (np.asarray(a, np.float64) for a in (got, ref, x0))
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    err = np.abs(got - ref)
+    upd = ref - x0
+    mx = err.max() / max(np.abs(upd).max(), 1e-30)
+    rms_err = np.sqrt(np.mean(err ** 2))
+    rms_upd, rms_out = np.sqrt(np.mean(upd ** 2)), np.sqrt(np.mean(ref ** 2))
+    bound = DRIFT_RMS * rms_upd + np.sqrt(2.0 * depth) * 2.0 ** -9 * rms_out
+    print(f"[drift] {what}: depth {depth}: max|err|/max|update|={mx:.3e} (of max|output|: {err.max() / np.abs(ref).max():.3e}) "
+          f"rms_err/rms_update={rms_err / max(rms_upd, 1e-30):.3e} rms_err/rms_output={rms_err / max(rms_out, 1e-30):.3e}", flush=True)
+    assert mx <= DRIFT_MAX, f"{what}: drift {mx:.3e} of the largest accumulated update > {DRIFT_MAX}"
+    assert rms_err <= bound, f"{what}: rms drift {rms_err:.3e} > {bound:.3e}"
+    return mx
+
+
+def assert_keep_set(keep_gpu, keep_ref, scores_ref, what="keep-set"):
+    """The keep-set is an integer decision on fp32 scores.  It must equal the oracle's unless scores
+    at the K-th place are closer than the fp32 summation noise of the score kernel; then the indices
+    the two sets disagree on must all sit at that threshold (and the sizes agree), so what is unique is
+    compared exactly and the rest is checked to be a valid choice."""
+    keep_gpu = np.asarray(keep_gpu).reshape(-1)
+    keep_ref = np.asarray(keep_ref).reshape(-1)
+    sc = np.asarray(scores_ref, np.float64).reshape(-1)
+    K = keep_ref.size
+    assert keep_gpu.size == K, f"{what}: {keep_gpu.size} indices, expected {K}"
+    assert np.all(np.diff(keep_gpu) > 0), f"{what}: not strictly ascending"
+    assert keep_gpu.min() >= 0 and keep_gpu.max() < sc.size, f"{what}: index out of range"
+    diff = np.setxor1d(keep_gpu, keep_ref)
+    if diff.size:
+        thr = np.sort(sc)[::-1][K - 1]
+        assert np.all(np.abs(sc[diff] - thr) <= 1e-4 * abs(thr)), f"{what}: differs from the oracle's away from the threshold"
+    return diff.size == 0
 
 
 def to_np(t):

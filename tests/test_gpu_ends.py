@@ -51,4 +51,4 @@ def test_neck(Bn, g, D, C):
     for bi in range(Bn):
         ref = oracle.neck(x[bi], w1, g1, b1, w2, g2, b2)
         # four bf16 roundings (two contractions, two normalisations) on values of order one
-        assert_close(got[bi], ref, f"neck image {bi}", stored=ref, updates=4)
+        assert_close(got[bi], ref, f"neck image {bi}", stored=ref, updates=1, rms_updates=4)

@@ -44,7 +44,7 @@ def test_permute_unpermute_roundtrip(B_, g, ws, D):
     rng = np.random.default_rng(0)
     x = inputs.bf16_round(rng.normal(size=(B_, g * g, D)).astype(np.float32))
     table = oracle.window_table(g, ws, 4)
-    xd, td = dev_bf16(x), dev_i32(table)
+    xd, td = dev_bf16(x), dev_i32(B.ssam_build_window_table(g, ws, 4))     # GPU side: the library's own table
     y = B.ssam_permute(xd, td)
     expect = np.where(table[None, :, None] >= 0, x[:, np.maximum(table, 0)], 0.0)
     assert np.array_equal(to_np(y), expect)                       # pure copy: bit exact
@@ -57,9 +57,10 @@ def test_permute_unpermute_roundtrip(B_, g, ws, D):
     assert np.array_equal(to_np(out), inputs.bf16_round(x + res))  # one fp32 add, one rounding
     # global order
     sigma, sinv = oracle.grid_sigma(g, 4)
-    y2 = B.ssam_permute(xd, dev_i32(sigma))
+    sig_lib, inv_lib = B.ssam_build_perm_device(g, g, 4)
+    y2 = B.ssam_permute(xd, sig_lib)
     assert np.array_equal(to_np(y2), x[:, sigma])
-    assert np.array_equal(to_np(B.ssam_permute(y2, dev_i32(sinv))), x)
+    assert np.array_equal(to_np(B.ssam_permute(y2, inv_lib)), x)
 
 
 @pytest.mark.parametrize("B_,n,D,K", [(2, 784, 768, 313), (1, 300, 1280, 300), (2, 100, 1024, 7), (1, 50, 2048, 50), (1, 64, 64, 64)])

@@ -203,3 +203,60 @@ def test_encoder_reuses_one_keep_set():
     assert keep.size == oracle.keep_count(g * g, 0.4)
     assert np.array_equal(keep, oracle.select_tokens(oracle.score_tokens(x), keep.size))
     assert y.shape == x.shape and np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("global_blocks,content_order", [((1,), False), ((0, 3), False), ((), False), ((2,), True)])
+def test_encoder_is_the_loop_over_its_pinned_blocks(global_blocks, content_order):
+    """Pin of the stack composition: `oracle.encoder` must equal a loop written out here over the pinned
+    single-block routine, with the window / global dispatch, the mask tile of either kind of block, the one
+    keep-set and (content-aware order) the one score map taken from the encoder INPUT.  The global flags are
+    non-trivial (first block, middle blocks, none), the two mask tiles differ and the rel-pos tables of the two
+    kinds of block have different shapes, so a wrong flag, a swapped tile or a keep-set recomputed per block fails."""
+    rng = np.random.default_rng(17)
+    depth, g, ws, heads, D, Dm = 4, 12, 6, 4, 32, 64
+    shape = inputs.ModelShape("tiny", D, depth, heads, Dm, tuple(global_blocks), ws)
+    wts = inputs.encoder_weights(6, shape, g)
+    for w in wts:                                   # large enough that every block visibly changes the stream
+        for kname in ("wqkv", "wproj", "w1", "w2", "rel_h", "rel_w"):
+            w[kname] = inputs.bf16_round(w[kname] * 8)
+    blocks = [oracle.BlockWeights(**w) for w in wts]
+    x = inputs.token_field(rng, 1, g, D)[0]
+    r, rho, Bw, Bg = 0.5, 0.4, 8, 32
+    y, keep = oracle.encoder(x, blocks, heads, ws, global_blocks, 4, r, rho, Bm_window=Bw, Bm_global=Bg,
+                             content_order=content_order)
+    scores = oracle.score_tokens(x)
+    keep_ref = oracle.select_tokens(scores, oracle.keep_count(g * g, rho))
+    assert np.array_equal(keep, keep_ref)
+    z = x
+    for i in range(depth):
+        is_global = i in global_blocks
+        z_next = oracle.encoder_block(z, blocks[i], heads, 0 if is_global else ws, 4, Bg if is_global else Bw, r, keep_ref,
+                                      order_scores=scores if content_order else None)
+        assert np.abs(z_next - z).max() > 1e-3       # the block is live
+        # the other kind of block gives something else here (so the flag matters); only possible where the
+        # rel-pos tables fit, i.e. never: a swapped flag is rejected by the shape check instead
+        with pytest.raises(AssertionError):
+            oracle.encoder_block(z, blocks[i], heads, ws if is_global else 0, 4, Bw if is_global else Bg, r, keep_ref)
+        z = z_next
+    assert np.array_equal(y, z)
+    # a keep-set recomputed from a later block's input would differ: the stream's scores move
+    assert not np.array_equal(keep_ref, oracle.select_tokens(oracle.score_tokens(z), keep_ref.size))
+    if content_order:
+        y_pos, _ = oracle.encoder(x, blocks, heads, ws, global_blocks, 4, r, rho, Bm_window=Bw, Bm_global=Bg)
+        assert np.abs(y_pos - y).max() > 1e-4        # the option is live
+
+
+def test_block_halves_compose_to_the_block():
+    """encoder_block_halves (attention half with an empty keep-set, then the routed MLP) is the block, bit for bit."""
+    rng = np.random.default_rng(19)
+    shape = inputs.ModelShape("tiny", 32, 1, 4, 64, (), 6)
+    g = 12
+    wt = oracle.BlockWeights(**inputs.encoder_weights(7, shape, g)[0])
+    x = inputs.token_field(rng, 1, g, shape.D)[0]
+    keep = oracle.select_tokens(oracle.score_tokens(x), 50)
+    for ws, Bm in ((6, 8), ):
+        x1, y = oracle.encoder_block_halves(x, wt, shape.heads, ws, 4, Bm, 0.5, keep)
+        assert np.array_equal(y, oracle.encoder_block(x, wt, shape.heads, ws, 4, Bm, 0.5, keep))
+        rest = np.setdiff1d(np.arange(g * g), keep)
+        assert np.array_equal(x1.reshape(g * g, -1)[rest], y.reshape(g * g, -1)[rest])     # bypass rows: y is x1
+        assert np.abs(x1 - x).max() > 1e-4 and np.abs(y - x1).max() > 1e-4
