@@ -237,7 +237,7 @@ int ssam_linear_ln(const void *x, int ldx, const float *stats, const void *Wfp, 
  *   out      dev bf16, rows of h*d: query p of group g is written to row g*S+p, or, with
  *            out_rows dev int32 [groups*S] != NULL, to row out_rows[g*S+p] (negative: not
  *            written; used to drop the padding queries of windows and compact the rest)
- * Built for d in {64, 80} (d % 16 == 0, d <= 96 accepted), mask_block = 32 with
+ * Built for d in {16, 32, 64, 80} (SAM uses 64 and 80), mask_block = 32 with
  * S <= 224 (windows) and mask_block = 128 with S <= 16384 (global); otherwise
  * SSAM_EUNSUPPORTED. */
 int ssam_sparse_attention(const void *q, const void *k, const void *v, long row_stride,

