@@ -257,6 +257,17 @@ size_t ssam_score_tokens_workspace_bytes(int B, int gh, int gw);
 int ssam_score_tokens(const void *x, float *scores, int B, int gh, int gw, int D,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* ssam_score_tokens for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same result bit for bit;
+ * the channel-sum map (4 bytes per token) is held in a device array that is part of the library (1 MiB on every
+ * GPU the library is loaded on, until the process ends), so at most SSAM_SCORE_TOKENS_STATIC_MAX_TOKENS =
+ * B*gh*gw tokens per call; more returns SSAM_EWORKSPACE and enqueues nothing.  Calls no allocator.  The first
+ * call on a device looks the array's address up (a host-side query: make that call outside any capture).  All
+ * calls on one GPU share the array: calls that overlap there (different streams or threads) race; calls on one
+ * stream do not. */
+#define SSAM_SCORE_TOKENS_STATIC_MAX_TOKENS (1 << 18)
+int ssam_score_tokens_static(const void *x, float *scores, int B, int gh, int gw, int D, void *stream);
+
 /* Keep-set: per batch item the K highest scores, ties to the lower index
  * (-0.0 == +0.0; NaN ranks as -inf), written in ascending index order.
  * scores dev fp32 [B][N]; keep_idx dev int32 [B][K]; 1 <= K <= N <= 65536. */

@@ -251,6 +251,14 @@ def ssam_score_tokens(x, scores=None, workspace=None):
     return scores
 
 
+def ssam_score_tokens_static(x, scores):
+    """The allocation-free entry point: `scores` [B, gh*gw] fp32 is the caller's; no workspace."""
+    B, gh, gw, D = x.shape
+    _check("ssam_score_tokens_static", lib().ssam_score_tokens_static(_bf(x, "x"), _f32(scores, "scores"), C.c_int(B),
+                                                                      C.c_int(gh), C.c_int(gw), C.c_int(D), _stream()))
+    return scores
+
+
 def ssam_select_tokens(scores, K, keep_idx=None):
     B, N = scores.shape
     if keep_idx is None:

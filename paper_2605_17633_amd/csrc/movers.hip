@@ -545,6 +545,50 @@ extern "C" int ssam_score_tokens(const void *x, float *scores, int B, int gh, in
     return SSAM_OK;
 }
 
+// ---- ssam_score_tokens for callers that cannot allocate: the channel-sum map lives in a file-scope device array.
+// In host code the array's name is only a stand-in; its device address is looked up once per device and kept.
+static __device__ __align__(256) float scratch[SSAM_SCORE_TOKENS_STATIC_MAX_TOKENS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float *scratch_ptr[kMaxDevices];        // device address of `scratch` on each GPU this process has used it on
+
+int scratch_on_current_device(float **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSAM_EHIP;
+    float *p = __atomic_load_n(&scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {                           // first call on this device (racing first calls resolve the same address)
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return SSAM_EHIP;
+        p = (float *)sym;
+        __atomic_store_n(&scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return SSAM_OK;
+}
+}  // namespace
+
+extern "C" int ssam_score_tokens_static(const void *x, float *scores, int B, int gh, int gw, int D, void *stream)
+{
+    if (!x || !scores || B <= 0 || gh <= 0 || gw <= 0 || D <= 0 || D % 8 != 0) return SSAM_EINVAL;
+    if (!ssam_aligned16(x)) return SSAM_EINVAL;
+    const long tokens = (long)B * gh * gw;
+    if (tokens > SSAM_SCORE_TOKENS_STATIC_MAX_TOKENS) return SSAM_EWORKSPACE;
+    float *csum = nullptr;
+    int rc = scratch_on_current_device(&csum);
+    if (rc != SSAM_OK) return rc;
+    // channel_sum_kernel writes the sum of every token it is given and sobel_kernel reads only those, so nothing
+    // in the array has to start at zero and what an earlier (larger) call left behind is never read
+    hipLaunchKernelGGL(channel_sum_kernel, dim3(ssam_div_up(tokens, 4)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)x, csum, tokens, D / 8);
+    SSAM_CHECK_LAUNCH();
+    hipLaunchKernelGGL(sobel_kernel, dim3(ssam_div_up(tokens, 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const float *)csum, scores, B, gh, gw);
+    SSAM_CHECK_LAUNCH();
+    return SSAM_OK;
+}
+
 extern "C" int ssam_select_tokens(const float *scores, int32_t *keep_idx, int B, int N, int K, void *stream)
 {
     if (!scores || !keep_idx || B <= 0 || N <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
