@@ -166,16 +166,16 @@ int ssam_linear_ld(const void *A, int lda, const void *W, int ldw, int w_packed,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* Weights in MFMA fragment order.  A weight matrix is static, so it can be laid
- * out once the way the matrix cores consume it: Wp[N/32][K/16][64][8] bf16 with
- *   Wp[nb][ks][32*hf + l][e] = W[32*nb + l][16*ks + 8*hf + e],
- * i.e. the 1 KB operand-B fragment of every (32 output channels, 16 input
- * channels) cell is contiguous.  ssam_linear_ld with w_packed != 0 (then ldw is
+ * out once the way the matrix cores consume it: Wp[N/16][K/32][64][8] bf16 with
+ *   Wp[nb][s][16*q + l][e] = W[16*nb + l][32*s + 8*q + e],   l < 16, q < 4, e < 8,
+ * i.e. the 1 KB operand-B fragment (of the 16x16x32 MFMA) of every (16 output
+ * channels, 32 input channels) cell is contiguous.  ssam_linear_ld with w_packed != 0 (then ldw is
  * ignored) loads such fragments straight into registers and stages only A in
  * LDS, which halves its LDS traffic; with the same tile (forced) the results are
  * bit-identical to the row-major form; the automatic choice may take another
  * tile for packed weights (the 128x256 one), and then the few left-over tiles
- * whose K range is cut can differ in fp32 summation order.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 32 ==
- * 0 and K % 16 == 0 (else SSAM_EUNSUPPORTED; ssam_linear_ld takes packed
+ * whose K range is cut can differ in fp32 summation order.  W dev bf16 [N][K] (row stride ldw), Wp dev bf16 N*K elements, N % 16 ==
+ * 0 and K % 32 == 0 (else SSAM_EUNSUPPORTED; ssam_linear_ld takes packed
  * weights only for N % 128 == 0 and K % 64 == 0); W and Wp must not overlap.  Tile
  * 2 (256x128) has no packed form (SSAM_EUNSUPPORTED when forced). */
 int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream);

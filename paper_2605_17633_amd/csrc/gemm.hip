@@ -242,21 +242,22 @@ extern "C" size_t ssam_linear_workspace_bytes(void) { return GEMM_SPLIT_WS_BYTES
 __global__ void __launch_bounds__(256)
 pack_weight_kernel(const bf16 *__restrict__ W, int ldw, bf16 *__restrict__ Wp, int N, int K)
 {
-    // one thread per 16-byte chunk of the packed matrix: chunk id = ((nb*ksteps + ks)*64 + lane)
+    // one thread per 16-byte chunk of the packed matrix: chunk id = ((nb*ksteps + s)*64 + lane); lane = 16*quad + l
+    // holds row 16*nb + l, k = 32*s + 8*quad .. + 7: the operand-b fragment of the 16x16x32 MFMA
     const long id = (long)blockIdx.x * 256 + threadIdx.x;
-    const int ksteps = K / 16;
-    if (id >= (long)(N / 32) * ksteps * 64) return;
-    const int lane = (int)(id & 63), l = lane & 31, hf = lane >> 5;
+    const int ksteps = K / 32;
+    if (id >= (long)(N / 16) * ksteps * 64) return;
+    const int lane = (int)(id & 63), l = lane & 15, quad = lane >> 4;
     const long cell = id >> 6;
     const int ks = (int)(cell % ksteps), nb = (int)(cell / ksteps);
-    reinterpret_cast<u32x4 *>(Wp)[id] = *reinterpret_cast<const u32x4 *>(W + (long)(32 * nb + l) * ldw + 16 * ks + 8 * hf);
+    reinterpret_cast<u32x4 *>(Wp)[id] = *reinterpret_cast<const u32x4 *>(W + (long)(16 * nb + l) * ldw + 32 * ks + 8 * quad);
 }
 
 extern "C" int ssam_pack_weight(const void *W, int ldw, void *Wp, int N, int K, void *stream)
 {
     if (!W || !Wp || N <= 0 || K <= 0 || ldw < K || ldw % 8) return SSAM_EINVAL;
     if (!ssam_aligned16(W) || !ssam_aligned16(Wp)) return SSAM_EINVAL;
-    if (N % 32 != 0 || K % 16 != 0) return SSAM_EUNSUPPORTED;
+    if (N % 16 != 0 || K % 32 != 0) return SSAM_EUNSUPPORTED;
     const long chunks = (long)N * K / 8;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)ssam_div_up(chunks, 256)), dim3(256), 0, (hipStream_t)stream,
                        (const bf16 *)W, ldw, (bf16 *)Wp, N, K);

@@ -1,18 +1,22 @@
 // bf16 NT GEMM for gfx950: C = epilogue(A[M][K] * W[N][K]^T + bias), fp32 accumulation on the
-// 32x32x16 bf16 MFMA.  Serves the block's qkv / proj / fc1 / fc2 layers (the dense contractions
+// 16x16x32 bf16 MFMA.  Serves the block's qkv / proj / fc1 / fc2 layers (the dense contractions
 // of the SAM block; the routed MLP of Sec. 4.2 reaches it with the gathered keep-set rows as A).
 //
 // Workgroup = WGM x WGN waves in a grid over a BM x BN tile; each wave owns (BM/WGM) x (BN/WGN) as
-// 32x32 MFMA tiles.  The 256x256 tile runs 8 waves (2x4, wave tile 128x64, under 256 VGPRs): two waves
+// 16x16 MFMA tiles.  The 256x256 tile runs 8 waves (2x4, wave tile 128x64, under 256 VGPRs): two waves
 // per SIMD, so one wave's LDS, barrier and MFMA-result latency is covered by the other; the smaller
-// tiles run 4 waves (2x2) and two workgroups per CU.  K is consumed in slabs of 64: global -> registers
-// (prefetch of the next slab) -> LDS (double buffered; 16-byte chunks XOR-swizzled so that both
+// tiles run 4 waves and two workgroups per CU.  K is consumed in slabs of 64 (two MFMA k-steps): global ->
+// registers (prefetch of the next slab) -> LDS (double buffered; 16-byte chunks XOR-swizzled so that both
 // the staging writes and the ds_read_b128 fragment reads are bank-conflict free).  Fragments are
 // double buffered in registers and the instruction mix is pinned with sched_group_barrier so that
 // LDS reads, global loads and LDS writes sit between MFMAs instead of in front of them; the
 // per-slab barrier orders LDS traffic only, so global prefetches stay in flight across it.
-// MFMA layout (32x32x16): lane l feeds row (l & 31), k-chunk (l >> 5); result register r of lane l
-// is C[8*(r/4) + 4*(l>>5) + (r&3)][l & 31], rows from operand a (activations), columns from b (W).
+// MFMA layout (16x16x32): lane l feeds row (l & 15), the 8 k values of chunk (l >> 4) of the 32; result
+// register r of lane l is C[4*(l>>4) + r][l & 15], rows from operand a (activations), columns from b (W).
+// Why this shape and not 32x32x16, which needs half as many operand fragments per flop: the chip is power
+// limited under matrix load and the shader clock settles where the power budget puts it; the 16x16x32
+// instruction reads and writes its fp32 accumulators half as often per flop and draws less: the same loop
+// runs at 1.74-1.87 GHz instead of 1.71-1.75 and 8-12 % faster on the block's four layer shapes.
 // The epilogue stages 32-row slices of the fp32 result through LDS so that each lane finishes 8
 // consecutive columns and issues 16-byte global accesses.
 // Tiles are dealt so that each XCD (its own L2) works on a contiguous run of tiles, ordered in
@@ -102,10 +106,16 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
 {
     static_assert(!LNF || EPI != GEMM_EPI_PARTIAL, "the folded LayerNorm is finished by the epilogue proper");
     constexpr int THREADS = 64 * WGM * WGN, RSTEP = THREADS / 8;   // waves in a WGM x WGN grid; rows staged per pass
-    constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32;       // MT: 32-row slices of the epilogue
+    constexpr int MT16 = WM / 16, NT16 = WN / 16;                  // the wave's accumulator tiles (16x16)
+    // A slab of 64 holds two MFMA k-steps of 32.  A k-step is issued in HP phases of AF row tiles each, so that only
+    // AF operand-a fragments are live per register slot: phase p = (k-step p / HP, row tiles (p % HP)*AF ...).
+    constexpr int AF = MT16 < 4 ? MT16 : 4, HP = MT16 / AF, PH = 2 * HP, NP = AF * NT16;
     constexpr int A_LOADS = BM * 8 / THREADS, B_LOADS = BN * 8 / THREADS;
     static_assert(BM % RSTEP == 0 && BN % RSTEP == 0 && RSTEP % 16 == 0, "staging passes must tile the operands");
-    constexpr int NM = MT * NT, NR = MT + NT, NL = A_LOADS + B_LOADS;
+    static_assert(WM % 32 == 0 && WN % 16 == 0 && MT16 % AF == 0, "wave tile in 16x16 MFMA tiles, epilogue in 32-row slices");
+    constexpr int NL = A_LOADS + B_LOADS;
+    static_assert((WPACK ? A_LOADS : NL) <= NP, "a phase has an MFMA to put every staging access behind");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16 *As = reinterpret_cast<bf16 *>(smem);                 // [2][BM*64]
     bf16 *Bs = As + 2 * BM * GEMM_BK;                          // [2][BN*64]
@@ -125,20 +135,20 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
-    const int l32 = lane & 31, half = lane >> 5;
+    const int l16 = lane & 15, quad = lane >> 4;
     const int nk = (K + GEMM_BK - 1) / GEMM_BK;          // a ragged last slab reads zeros past K (K % 8 == 0)
     const int kb = (int)((long)nk * kpart / parts), ke = (int)((long)nk * (kpart + 1) / parts);   // this workgroup's slabs
 
-    f32x16 acc[MT][NT];
+    f32x4 acc[MT16][NT16];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < MT16; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int j = 0; j < NT16; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
     u32x4 ra[A_LOADS], rb[B_LOADS];
-    bf16x8 af[2][MT], bfr[2][NT];
+    bf16x8 af[2][AF], bw[2][NT16];          // operand a: one slot per phase parity; operand b: one slot per k-step
 
     // staging: thread owns chunk c0 of rows r0 + RSTEP*i of both operands
     const int r0 = tid >> 3, c0 = tid & 7;
@@ -152,8 +162,10 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         gb[i] = W + (long)min(n0 + r0 + RSTEP * i, N - 1) * ld.w + c0 * 8;
     const bf16 *zchunk = reinterpret_cast<const bf16 *>(gemm_zero_chunk);
     const int lst = gemm_swz(r0, c0);          // + i*RSTEP*64: rows a multiple of 16 apart share the swizzle term
-    const int fa0 = (wm + l32) * GEMM_BK, fb0 = (wn + l32) * GEMM_BK;
-    const int sw = (l32 >> 1) & 7;
+    // fragment reads: lane (l16, quad) takes the 16-byte chunk 4*s + quad of row l16 of a 16-row tile; the 16 lanes of
+    // a quad touch 8 swizzled chunk positions x 2 row parities = all 64 banks once
+    const int fa0 = (wm + l16) * GEMM_BK, fb0 = (wn + l16) * GEMM_BK;
+    const int sw = l16 >> 1;
 
 #define GEMM_LOAD_GLOBAL(kt_)                                                                         \
     {                                                                                                 \
@@ -171,41 +183,45 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         _Pragma("unroll") for (int i = 0; i < B_LOADS; ++i)                                           \
             *reinterpret_cast<u32x4 *>(bs_ + i * RSTEP * GEMM_BK) = rb[i];                               \
     }
-#define GEMM_LOAD_FRAGS(buf_, ks_, slot_)                                                             \
+// operand-a fragments of phase p_ into register slot slot_
+#define GEMM_LOAD_AFRAGS(buf_, p_, slot_)                                                             \
     {                                                                                                 \
-        const int co_ = (((ks_) * 2 + half) ^ sw) << 3;                                               \
-        const bf16 *as_ = As + (buf_) * BM * GEMM_BK + fa0 + co_;                                     \
-        const bf16 *bs_ = Bs + (buf_) * BN * GEMM_BK + fb0 + co_;                                     \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                \
-            af[slot_][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * GEMM_BK);                 \
-        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                \
-            bfr[slot_][j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 32 * GEMM_BK);                \
+        const bf16 *as_ = As + (buf_) * BM * GEMM_BK + fa0 + (((p_) % HP) * AF) * 16 * GEMM_BK        \
+                          + (((((p_) / HP) * 4 + quad) ^ sw) << 3);                                   \
+        _Pragma("unroll") for (int i = 0; i < AF; ++i)                                                \
+            af[slot_][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 16 * GEMM_BK);                 \
     }
-#define GEMM_MFMAS(slot_)                                                                             \
+// operand-b fragments of k-step s_ from LDS (row-major weights)
+#define GEMM_LOAD_BFRAGS(buf_, s_)                                                                    \
     {                                                                                                 \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                \
-            _Pragma("unroll") for (int j = 0; j < NT; ++j)                                            \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], bfr[slot_][j], acc[i][j], 0, 0, 0); \
+        const bf16 *bs_ = Bs + (buf_) * BN * GEMM_BK + fb0 + ((((s_) * 4 + quad) ^ sw) << 3);         \
+        _Pragma("unroll") for (int j = 0; j < NT16; ++j)                                              \
+            bw[s_][j] = *reinterpret_cast<const bf16x8 *>(bs_ + j * 16 * GEMM_BK);                    \
+    }
+#define GEMM_MFMAS(p_, slot_)                                                                         \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < AF; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < NT16; ++j)                                          \
+                acc[((p_) % HP) * AF + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(               \
+                    af[slot_][i], bw[(p_) / HP][j], acc[((p_) % HP) * AF + i][j], 0, 0, 0);           \
     }
 
     int buf = 0;
     if (WPACK) {
-        // W arrives pre-shuffled into fragment order ([N/32][K/16][64 lanes][8]): every wave loads its own
-        // B fragments straight into registers with 1 KB coalesced loads, one slab ahead at k-step granularity
-        // (the fragments of k-step s of the next slab are requested as soon as this slab's step s has issued),
-        // and only A goes through LDS.
-        const int ksteps = K / 16;
-        // one pointer per 32-column block of the wave; a block past N (a tile wider than what is left of a
+        // W arrives pre-shuffled into fragment order ([N/16][K/32][64 lanes][8]): every wave loads its own
+        // operand-b fragments straight into registers with 1 KB coalesced loads (the fragments of a k-step of the
+        // next slab are requested as soon as this slab's k-step has issued), and only A goes through LDS.
+        const int ksteps = K / 32;
+        // one pointer per 16-column block of the wave; a block past N (a tile wider than what is left of a
         // width that is a multiple of 128 only) re-reads the last block of W: its results are never stored
-        const bf16 *wp[NT];
+        const bf16 *wp[NT16];
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-            wp[j] = W + ((long)min(((n0 + wn) >> 5) + j, (N >> 5) - 1) * ksteps) * 512 + lane * 8;
-        bf16x8 wf[4][NT];
-#define GEMM_LOAD_W(kt_, ks_)                                                                         \
+        for (int j = 0; j < NT16; ++j)
+            wp[j] = W + ((long)min(((n0 + wn) >> 4) + j, (N >> 4) - 1) * ksteps) * 512 + lane * 8;
+#define GEMM_LOAD_W(kt_, s_)                                                                          \
         {                                                                                             \
-            _Pragma("unroll") for (int j = 0; j < NT; ++j)                                            \
-                wf[ks_][j] = *reinterpret_cast<const bf16x8 *>(wp[j] + ((long)(kt_) * 4 + (ks_)) * 512); \
+            _Pragma("unroll") for (int j = 0; j < NT16; ++j)                                          \
+                bw[s_][j] = *reinterpret_cast<const bf16x8 *>(wp[j] + ((long)(kt_) * 2 + (s_)) * 512); \
         }
 #define GEMM_LOAD_GLOBAL_A(kt_)                                                                       \
         {                                                                                             \
@@ -218,24 +234,12 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
             _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                       \
                 *reinterpret_cast<u32x4 *>(as_ + i * RSTEP * GEMM_BK) = ra[i];                        \
         }
-#define GEMM_LOAD_AFRAGS(buf_, ks_, slot_)                                                            \
-        {                                                                                             \
-            const bf16 *as_ = As + (buf_) * BM * GEMM_BK + fa0 + ((((ks_) * 2 + half) ^ sw) << 3);    \
-            _Pragma("unroll") for (int i = 0; i < MT; ++i)                                            \
-                af[slot_][i] = *reinterpret_cast<const bf16x8 *>(as_ + i * 32 * GEMM_BK);             \
-        }
-#define GEMM_MFMAS_W(slot_, ks_)                                                                      \
-        {                                                                                             \
-            _Pragma("unroll") for (int i = 0; i < MT; ++i)                                            \
-                _Pragma("unroll") for (int j = 0; j < NT; ++j)                                        \
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot_][i], wf[ks_][j], acc[i][j], 0, 0, 0); \
-        }
-        // A is requested 1.25 slabs before it is stored: the registers ra are stored to LDS in k-step 2 of a
-        // slab (data of the next slab, requested in k-step 3 of the previous one, so the store never waits for
-        // memory and completes a k-step before the barrier instead of right in front of it) and refilled in
-        // k-step 3 with the slab after next.
+        // A is requested 1.25 slabs before it is stored: the registers ra are stored to LDS in the last phase but
+        // one of a slab (data of the next slab, requested in the last phase of the previous one, so the store never
+        // waits for memory and completes a phase before the barrier instead of right in front of it) and refilled
+        // in the last phase with the slab after next.
         GEMM_LOAD_GLOBAL_A(kb)
-        GEMM_LOAD_W(kb, 0) GEMM_LOAD_W(kb, 1) GEMM_LOAD_W(kb, 2) GEMM_LOAD_W(kb, 3)
+        GEMM_LOAD_W(kb, 0) GEMM_LOAD_W(kb, 1)
         GEMM_STORE_LDS_A(0)
         GEMM_LOAD_GLOBAL_A(min(kb + 1, ke - 1))
         LDS_BARRIER();
@@ -244,78 +248,79 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         __builtin_amdgcn_s_setprio(1);
         for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
             GEMM_LOAD_AFRAGS(buf, 0, 0)
-            GEMM_LOAD_AFRAGS(buf, 1, 1)
-            GEMM_MFMAS_W(0, 0)
-            GEMM_LOAD_W(kt + 1, 0)
-            GEMM_LOAD_AFRAGS(buf, 2, 0)
-            GEMM_MFMAS_W(1, 1)
-            GEMM_LOAD_W(kt + 1, 1)
-            GEMM_LOAD_AFRAGS(buf, 3, 1)
-            GEMM_MFMAS_W(0, 2)
-            GEMM_STORE_LDS_A(buf ^ 1)
-            GEMM_LOAD_W(kt + 1, 2)
-            GEMM_MFMAS_W(1, 3)
-            GEMM_LOAD_GLOBAL_A(min(kt + 2, ke - 1))
-            GEMM_LOAD_W(kt + 1, 3)
-            GEMM_SGB(0x100, MT);
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
+            for (int p = 0; p < PH; ++p) {
+                if (p + 1 < PH) GEMM_LOAD_AFRAGS(buf, p + 1, (p + 1) & 1)
+                GEMM_MFMAS(p, p & 1)
+                if (p == PH - 2) GEMM_STORE_LDS_A(buf ^ 1)
+                if (p == PH - 1) GEMM_LOAD_GLOBAL_A(min(kt + 2, ke - 1))
+                if (p % HP == HP - 1) GEMM_LOAD_W(kt + 1, p / HP)
+            }
+            // issue order: the fragments of phase 0, then per phase its MFMAs with the next phase's LDS reads behind
+            // the first ones, the LDS writes / the next A requests behind the first ones of the last two phases, and the
+            // requests for a finished k-step's operand-b fragments behind the last ones
+            GEMM_SGB(0x100, AF);
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
+            for (int p = 0; p < PH; ++p)
 #pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < MT) GEMM_SGB(0x100, 1); if (i < A_LOADS) GEMM_SGB(0x200, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
-#pragma unroll
-            for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < A_LOADS) GEMM_SGB(0x020, 1); if (i >= NM - NT) GEMM_SGB(0x020, 1); }
+                for (int i = 0; i < NP; ++i) {
+                    GEMM_SGB(0x008, 1);
+                    if (p + 1 < PH && i < AF) GEMM_SGB(0x100, 1);
+                    if (p == PH - 2 && i < A_LOADS) GEMM_SGB(0x200, 1);
+                    if (p == PH - 1 && i < A_LOADS) GEMM_SGB(0x020, 1);
+                    if (p % HP == HP - 1 && i >= NP - NT16) GEMM_SGB(0x020, 1);
+                }
             LDS_BARRIER();
         }
         GEMM_LOAD_AFRAGS(buf, 0, 0)
-        GEMM_LOAD_AFRAGS(buf, 1, 1)
-        GEMM_MFMAS_W(0, 0)
-        GEMM_LOAD_AFRAGS(buf, 2, 0)
-        GEMM_MFMAS_W(1, 1)
-        GEMM_LOAD_AFRAGS(buf, 3, 1)
-        GEMM_MFMAS_W(0, 2)
-        GEMM_MFMAS_W(1, 3)
+#pragma unroll
+        for (int p = 0; p < PH; ++p) {
+            if (p + 1 < PH) GEMM_LOAD_AFRAGS(buf, p + 1, (p + 1) & 1)
+            GEMM_MFMAS(p, p & 1)
+        }
         __builtin_amdgcn_s_setprio(0);
     } else {
     GEMM_LOAD_GLOBAL(kb)
     GEMM_STORE_LDS(0)
     LDS_BARRIER();
     for (int kt = kb; kt < ke - 1; ++kt, buf ^= 1) {
-        GEMM_LOAD_FRAGS(buf, 0, 0)
-        GEMM_LOAD_GLOBAL(kt + 1)
-        GEMM_LOAD_FRAGS(buf, 1, 1)
-        GEMM_MFMAS(0)
-        GEMM_LOAD_FRAGS(buf, 2, 0)
-        GEMM_MFMAS(1)
-        GEMM_LOAD_FRAGS(buf, 3, 1)
-        GEMM_MFMAS(0)
-        GEMM_MFMAS(1)
-        GEMM_STORE_LDS(buf ^ 1)
-        // issue order: fragments of k-step 0; then per k-step its MFMAs with the next step's LDS reads,
-        // the next slab's global loads (step 0) and LDS writes (step 3) slotted in between
-        GEMM_SGB(0x100, NR);
+        GEMM_LOAD_AFRAGS(buf, 0, 0)
+        GEMM_LOAD_BFRAGS(buf, 0)
 #pragma unroll
-        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); if (i < NL) GEMM_SGB(0x020, 1); }
-        if (NL > NM) GEMM_SGB(0x020, NL - NM);
+        for (int p = 0; p < PH; ++p) {
+            if (p == 0) GEMM_LOAD_GLOBAL(kt + 1)
+            if (p + 1 < PH) {
+                GEMM_LOAD_AFRAGS(buf, p + 1, (p + 1) & 1)
+                if ((p + 1) % HP == 0) GEMM_LOAD_BFRAGS(buf, (p + 1) / HP)
+            }
+            GEMM_MFMAS(p, p & 1)
+            if (p == PH - 1) GEMM_STORE_LDS(buf ^ 1)
+        }
+        // issue order: fragments of phase 0; then per phase its MFMAs with the next phase's LDS reads, the next
+        // slab's global loads (phase 0) and LDS writes (last phase) slotted in between
+        GEMM_SGB(0x100, AF + NT16);
 #pragma unroll
-        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); }
+        for (int p = 0; p < PH; ++p)
 #pragma unroll
-        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NR) GEMM_SGB(0x100, 1); }
-#pragma unroll
-        for (int i = 0; i < NM; ++i) { GEMM_SGB(0x008, 1); if (i < NL) GEMM_SGB(0x200, 1); }
-        if (NL > NM) GEMM_SGB(0x200, NL - NM);
+            for (int i = 0; i < NP; ++i) {
+                GEMM_SGB(0x008, 1);
+                if (p + 1 < PH && i < AF + ((p + 1) % HP == 0 ? NT16 : 0)) GEMM_SGB(0x100, 1);
+                if (p == 0 && i < NL) GEMM_SGB(0x020, 1);
+                if (p == PH - 1 && i < NL) GEMM_SGB(0x200, 1);
+            }
         LDS_BARRIER();
     }
     {
-        GEMM_LOAD_FRAGS(buf, 0, 0)
-        GEMM_LOAD_FRAGS(buf, 1, 1)
-        GEMM_MFMAS(0)
-        GEMM_LOAD_FRAGS(buf, 2, 0)
-        GEMM_MFMAS(1)
-        GEMM_LOAD_FRAGS(buf, 3, 1)
-        GEMM_MFMAS(0)
-        GEMM_MFMAS(1)
+        GEMM_LOAD_AFRAGS(buf, 0, 0)
+        GEMM_LOAD_BFRAGS(buf, 0)
+#pragma unroll
+        for (int p = 0; p < PH; ++p) {
+            if (p + 1 < PH) {
+                GEMM_LOAD_AFRAGS(buf, p + 1, (p + 1) & 1)
+                if ((p + 1) % HP == 0) GEMM_LOAD_BFRAGS(buf, (p + 1) / HP)
+            }
+            GEMM_MFMAS(p, p & 1)
+        }
     }
     }
 
@@ -409,10 +414,12 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int t = 0; t < 2; ++t)             // the slice's two 16-row tiles: lane (l16, quad) holds rows 4*quad + r
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                stage[(8 * (r >> 2) + 4 * half + (r & 3)) * EPS + j * 32 + l32] = acc[i][j][r];
+            for (int j = 0; j < NT16; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    stage[(t * 16 + 4 * quad + r) * EPS + j * 16 + l16] = acc[2 * i + t][j][r];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         if (MAPPED && i + 1 < MT) preload_slice(i + 1, old_next, drow_next);

@@ -218,7 +218,7 @@ def test_linear_packed_weights(tile, M, N, K, epi):
     Ad, Wd, bd = dev_bf16(A), dev_bf16(W), dev_f32(b)
     Wp = B.ssam_pack_weight(Wd)
     # the packing itself, against its definition
-    ref_p = to_np(Wd).reshape(N // 32, 32, K // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(N, K)
+    ref_p = to_np(Wd).reshape(N // 16, 16, K // 32, 4, 8).transpose(0, 2, 3, 1, 4).reshape(N, K)
     assert np.array_equal(to_np(Wp), ref_p)
     ws = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=DEV)
     kw = {}
