@@ -97,18 +97,23 @@ __device__ __forceinline__ void init_state(WaveState<D> &st)
     st.l = 0.f;
 }
 
-// Bias tables of the wave's 32 queries, 2*ts entries per query, stored entry-major so that the 32 lanes
-// that look up the same key (a key's row and column are the same for every query) hit consecutive banks:
-//   tq[p*32 + q]        = log2e * q . rel_h[row(q)-p+w-1]      (p = key row)
-//   tq[(ts + p)*32 + q] = log2e * q . rel_w[col(q)-p+w-1]      (p = key column)
-// rel tables: rows of `rstr` elements in global memory.
+// Bias table of the wave's 32 queries in the global kernel, query-major, fp16 (see GlbTab), divided by the softmax
+// scale so that (score + row entry + column entry) * scale * log2e is the logit in log2 units:
+//   tq[q*tstr + (p&1)*hw + (p>>1)]            = q . rel_h[row(q)-p+w-1] / scale      (p = key row)
+//   tq[q*tstr + 2*hw + (p&1)*hw + (p>>1)]     = q . rel_w[col(q)-p+w-1] / scale      (p = key column)
+// hw = ceil(w/2): even and odd rows (columns) are stored apart, so that rows two apart are neighbours: the 32-key
+// blocks of the position-only Stripe-Sort order are 4 x 8 patches of stride 2 (see attn_scores_patch), whose 4 row
+// and 8 column entries are then contiguous.  tstr = 4*hw + 4: the 8 bytes of padding put the 32 lanes of a look-up
+// (one entry, 32 queries) on distinct banks.  tq_lane: this lane's query row.  rel tables: rows of `rstr` elements.
+__host__ __device__ inline int glb_tstr(int w) { return 4 * ((w + 1) >> 1) + 4; }
+
 template <int D, typename TabT>
 __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *rel_h, const bf16 *rel_w, int rstr,
-                                                int w, int qrow, int qcol, TabT *tq, int ts)
+                                                int w, int qrow, int qcol, TabT *tq_lane, float inv_scale)
 {
     constexpr int KS = AttnCfg<D>::KS;
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
-    const int nrel = 2 * w - 1;
+    const int nrel = 2 * w - 1, hw = (w + 1) >> 1;
     // operand a of slab mt: rows mt*32 + l32 of both tables; rows past the table re-read its last row (their
     // products are never stored), so every load is unconditional and a slab's 2*KS loads are in flight together
     bf16x8 cur[2][KS], nxt[2][KS];
@@ -135,13 +140,13 @@ __device__ __forceinline__ void build_bias_rows(const bf16x8 *qf, const bf16 *re
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");          // MFMA passes done before u is read under predicates
             __builtin_amdgcn_sched_barrier(0);
-            TabT *dst = tq + (tab ? ts * 32 : 0) + l32;
+            TabT *dst = tq_lane + (tab ? 2 * hw : 0);
             const int qpos = tab ? qcol : qrow;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int m = mt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 int p = qpos + (w - 1) - m;
-                if (p >= 0 && p < w && m < nrel) dst[p * 32] = (TabT)(u[r] * LOG2E);
+                if (p >= 0 && p < w && m < nrel) dst[(p & 1) * hw + (p >> 1)] = (TabT)(u[r] * inv_scale);
             }
         }
 #pragma unroll
@@ -189,16 +194,88 @@ __device__ __forceinline__ void build_bias_rows_window(const bf16x8 *qf, const b
 // A chunk of nb (1..NB, wave-uniform) 32-key blocks against the wave's 32 queries.
 //   Ks, Vs: LDS, row-major rows ([keys][KSTR]); blk[b]: index of the chunk's b-th block in them
 //   krc:    LDS, per key two byte offsets into the bias tables, indexed like Ks: low half for the row part,
-//           high half for the column part (entry-major tables: 32*esz*row and 32*esz*(ts + col); window
-//           tables: the key's share of the entry index, see key_bias_offsets_window)
+//           high half for the column part (global kernel: within the query's table row, see build_bias_rows;
+//           window tables: the key's share of the entry index, see key_bias_offsets_window)
 //   key0[b]: scan position of the block's first key (for the S bound; RAGGED = the chunk crosses S)
 //   tq_h, tq_w: where this lane's query starts in the row-part and column-part bias tables; a key's two
 //           bias terms are read at tq_h + (low half of krc) and tq_w + (high half of krc), in bytes
 //   FULL:   the chunk has all NB blocks (nb is not looked at: no per-block branches, no dummy scores)
 //   MIXADD: the column part of the bias is added by one mixed-precision fma (fp16 operand widened inside the
 //           instruction) instead of convert + add
+//   RAW:    the tables hold bias / scale and the scores stay unscaled: logit = (s + bh + bw) * scale_log2e
+//           (global kernel); otherwise the tables hold bias * log2e and logit = s * scale_log2e + bh + bw
 constexpr float ATTN_LAG = 8.f;
-template <int D, int NB, bool RAGGED, bool FULL, typename TabT, bool MIXADD = false>
+
+// Second half of a chunk step, the same for every way of forming the scores: s holds the chunk's logits (RAW: before
+// the multiplication by scale_log2e), mx their maximum over this lane's keys, in the same units.
+template <int D, int NB, bool FULL, bool RAW>
+__device__ __forceinline__ void attn_softmax_pv(WaveState<D> &st, f32x16 (&s)[NB], float mx, const bf16 *Vs,
+                                                const int (&blk)[NB], int nb_, float scale_log2e)
+{
+    using C = AttnCfg<D>;
+    const int nb = FULL ? NB : nb_;
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if constexpr (RAW) mx *= scale_log2e;
+    // st.m is the exponent reference of the running sums, not the running maximum: it moves only when a chunk's
+    // maximum exceeds it by more than 2^ATTN_LAG, so probabilities stay below 2^ATTN_LAG (all of a query's terms
+    // carry the same power of two, which the final division removes) and the rescaling of the 32 x D accumulator
+    // is skipped by the whole wave in most chunks.  First chunk: st.m = -inf, every lane moves, alpha = 0.
+    const bool move = mx > st.m + ATTN_LAG;
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+        const float mnew = move ? mx : st.m;
+        const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
+        st.m = mnew;
+        if constexpr (!C::ONES) st.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
+    }
+    const float mref = st.m;
+    float psum = 0.f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[b][r] = __builtin_amdgcn_exp2f(RAW ? fmaf(s[b][r], scale_log2e, -mref) : s[b][r] - mref);
+                if constexpr (!C::ONES) psum += s[b][r];
+            }
+        }
+    }
+    if constexpr (!C::ONES) st.l += psum;
+    // transposing read: lane li of a 16-lane group points at row (li >> 2), column chunk (li & 3) of a
+    // 4-key x 16-feature block and receives the 4 keys of feature column li
+    const int li = lane & 15, fblk = (lane >> 4) & 1;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b < nb) {
+            const bf16 *vblk = Vs + blk[b] * 32 * C::KSTR + (4 * half + (li >> 2)) * C::KSTR;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                bf16x8 p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = (bf16)s[b][8 * t + e];
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt) {
+                    int col = dt * 32 + 16 * fblk + 4 * (li & 3);
+                    // feature columns past D re-read the last ones and their outputs are dropped; with ONES they are
+                    // the ones columns D .. D+7, and their outputs are the sums of the probabilities
+                    constexpr int CMAX = C::ONES ? D + 4 : D - 4;
+                    col = col <= CMAX ? col : CMAX;
+                    const bf16 *v0p = vblk + 16 * t * C::KSTR + col;
+                    bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p));
+                    bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p + 8 * C::KSTR));
+                    bf16x8 a = { v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3] };
+                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p, st.o[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+}
+
+template <int D, int NB, bool RAGGED, bool FULL, typename TabT, bool MIXADD = false, bool RAW = false>
 __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
                                                 const uint32_t *krc, const int (&blk)[NB], const int (&key0)[NB], int nb_,
                                                 int S, float scale_log2e, const TabT *tq_h, const TabT *tq_w)
@@ -247,11 +324,11 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
                     if constexpr (MIXADD) {
                         static_assert(sizeof(TabT) == 2, "bias tables are fp16");
                         const uint32_t bw16 = *reinterpret_cast<const uint16_t *>(tqw + (c >> 16));
-                        val = s[b][r] * scale_log2e + bh;            // the compiler forms this mixed fma by itself
+                        val = RAW ? s[b][r] + bh : s[b][r] * scale_log2e + bh;   // the compiler forms this mixed op by itself
                         asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(val) : "v"(bw16), "v"(val));
                     } else {
                         const float bw = (float)*reinterpret_cast<const TabT *>(tqw + (c >> 16));
-                        val = s[b][r] * scale_log2e + bh + bw;
+                        val = RAW ? s[b][r] + bh + bw : s[b][r] * scale_log2e + bh + bw;
                     }
                     if (RAGGED) val = (key0[b] + 8 * g + 4 * half + e < S) ? val : -INFINITY;
                     s[b][r] = val;
@@ -260,64 +337,60 @@ __device__ __forceinline__ void attn_chunk_step(WaveState<D> &st, const bf16x8 *
             }
         }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // st.m is the exponent reference of the running sums, not the running maximum: it moves only when a chunk's
-    // maximum exceeds it by more than 2^ATTN_LAG, so probabilities stay below 2^ATTN_LAG (all of a query's terms
-    // carry the same power of two, which the final division removes) and the rescaling of the 32 x D accumulator
-    // is skipped by the whole wave in most chunks.  First chunk: st.m = -inf, every lane moves, alpha = 0.
-    const bool move = mx > st.m + ATTN_LAG;
-    if (__builtin_amdgcn_ballot_w64(move) != 0) {
-        const float mnew = move ? mx : st.m;
-        const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
-        st.m = mnew;
-        if constexpr (!C::ONES) st.l *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st.o[dt][r] *= alpha;
-    }
-    const float mref = st.m;
-    float psum = 0.f;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b < nb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[b][r] = __builtin_amdgcn_exp2f(s[b][r] - mref);
-                if constexpr (!C::ONES) psum += s[b][r];
-            }
-        }
-    }
-    if constexpr (!C::ONES) st.l += psum;
-    // transposing read: lane li of a 16-lane group points at row (li >> 2), column chunk (li & 3) of a
-    // 4-key x 16-feature block and receives the 4 keys of feature column li
-    const int li = lane & 15, fblk = (lane >> 4) & 1;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (b < nb) {
-            const bf16 *vblk = Vs + blk[b] * 32 * C::KSTR + (4 * half + (li >> 2)) * C::KSTR;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                bf16x8 p;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) p[e] = (bf16)s[b][8 * t + e];
-#pragma unroll
-                for (int dt = 0; dt < C::DT; ++dt) {
-                    int col = dt * 32 + 16 * fblk + 4 * (li & 3);
-                    // feature columns past D re-read the last ones and their outputs are dropped; with ONES they are
-                    // the ones columns D .. D+7, and their outputs are the sums of the probabilities
-                    constexpr int CMAX = C::ONES ? D + 4 : D - 4;
-                    col = col <= CMAX ? col : CMAX;
-                    const bf16 *v0p = vblk + 16 * t * C::KSTR + col;
-                    bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p));
-                    bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(v0p + 8 * C::KSTR));
-                    bf16x8 a = { v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3] };
-                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p, st.o[dt], 0, 0, 0);
-                }
-            }
-        }
-    }
+    attn_softmax_pv<D, NB, FULL, RAW>(st, s, mx, Vs, blk, nb_, scale_log2e);
 }
+
+// Scores of a chunk whose 32-key blocks are 4 x 8 patches of stride 2 in the grid: key k of a block (bits c0 r1'.. in
+// scan order: bit 0 and bits 2, 4 count columns, bits 1 and 3 rows, i.e. a Z-order walk) sits 2*rr(k) rows and 2*cc(k)
+// columns from the block's first key.  That is how the position-only Stripe-Sort order (Sec. 4.1: Z-order, then the
+// stripe interleave with G = 4, which collects the cells of one row and column parity) lays out a power-of-two grid.
+// The decomposed bias of such a block is a product: B[k][q] = sum_f E[k][f] T[f][q] with E the 0/1 matrix that
+// picks a key's row entry (f = rr) and column entry (f = 4 + cc) and T the 4 row and 8 column entries of every
+// query, which are contiguous in the query's table row (build_bias_rows).  So the bias is ONE more MFMA (fp16
+// operands, the same fp32 accumulator, issued first) and the vector unit does no look-ups and no additions.
+//   efrag:  the lane's part of E (operand a; the same for every block)
+//   blkoff: LDS, per block of the tile the table offsets of its first key (as in krc)
+//   tq_lane: this lane's query row of the table
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+template <int D, int NB>
+__device__ __forceinline__ void attn_chunk_step_patch(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
+                                                      const uint32_t *blkoff, const int (&blk)[NB], const f16x8 &efrag,
+                                                      const unsigned char *tq_lane, float scale_log2e)
+{
+    using C = AttnCfg<D>;
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    f32x16 s[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        // operand b of the bias product: f = 8*half + e; f 0..3 the block's rows, 4..11 its columns, 12..15 meet zeros
+        // of E (whatever finite values the second read of the upper half-wave returns)
+        const uint32_t bo = blkoff[blk[b]];
+        const f16x4 t1 = *reinterpret_cast<const f16x4 *>(tq_lane + (half ? (bo >> 16) + 8 : (bo & 0xffffu)));
+        const f16x4 t2 = *reinterpret_cast<const f16x4 *>(tq_lane + (bo >> 16));
+        const f16x8 tf = { t1[0], t1[1], t1[2], t1[3], t2[0], t2[1], t2[2], t2[3] };
+        const f32x16 zero = { 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f };
+        s[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(efrag, tf, zero, 0, 0, 0);
+        const bf16 *kblk = Ks + blk[b] * 32 * C::KSTR + l32 * C::KSTR + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            bf16x8 a = *reinterpret_cast<const bf16x8 *>(kblk + ks * 16);
+            s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[b], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
+    attn_softmax_pv<D, NB, true, true>(st, s, mx, Vs, blk, NB, scale_log2e);
+}
+
+// row and column steps (in units of 2 cells) of key k of a patch block from the block's first key
+__device__ __forceinline__ int patch_rr(int k) { return ((k >> 1) & 1) | ((k >> 2) & 2); }
+__device__ __forceinline__ int patch_cc(int k) { return (k & 1) | ((k >> 1) & 2) | ((k >> 2) & 4); }
 
 template <int D, int NB, typename TabT>
 __device__ __forceinline__ void attn_chunk(WaveState<D> &st, const bf16x8 *qf, const bf16 *Ks, const bf16 *Vs,
@@ -399,11 +472,13 @@ __device__ __forceinline__ uint32_t key_row_col(const int32_t *sigma, int p, int
     return cell_row_col(sigma[p < S ? p : S - 1], w);
 }
 
-// byte offsets of a cell's two entries in the wave's entry-major bias tables (row part, then column part)
-__device__ __forceinline__ uint32_t cell_bias_offsets(int cell, int w, int ts, uint32_t esz)
+// byte offsets of a cell's two entries within a query's row of the global kernel's bias table (row part in the low
+// half, column part in the high half; see build_bias_rows)
+__device__ __forceinline__ uint32_t cell_bias_offsets(int cell, int w)
 {
-    uint32_t rc = cell_row_col(cell, w);
-    return (32u * esz * (rc & 0xffffu)) | ((32u * esz * ((uint32_t)ts + (rc >> 16))) << 16);
+    const uint32_t rc = cell_row_col(cell, w), esz = sizeof(_Float16);
+    const uint32_t hw = (uint32_t)(w + 1) >> 1, row = rc & 0xffffu, col = rc >> 16;
+    return (esz * ((row & 1) * hw + (row >> 1))) | ((esz * (2 * hw + (col & 1) * hw + (col >> 1))) << 16);
 }
 
 // window kernel: byte offsets of the key's entries within a query's two table rows, less the query's own part
@@ -414,11 +489,12 @@ __device__ __forceinline__ uint32_t key_bias_offsets_window(const int32_t *sigma
     return (esz * (uint32_t)(w - 1 - (int)(rc & 0xffffu))) | ((esz * (uint32_t)(w - 1 - (int)(rc >> 16))) << 16);
 }
 
-// per-wave LDS scratch: the bias rows of its 32 queries, later overlaid by its output staging tile
+// per-wave LDS scratch of the global kernel: the bias table of its 32 queries (rows of tstr fp16), later overlaid by
+// its output staging tile
 template <int D>
-__host__ __device__ inline int wave_scratch_bytes(int ts, int esz = 4)
+__host__ __device__ inline int wave_scratch_bytes(int tstr)
 {
-    int bias = 32 * 2 * ts * esz, stage = 32 * AttnCfg<D>::KSTR * 2;
+    int bias = 32 * tstr * 2, stage = 32 * AttnCfg<D>::KSTR * 2;
     return ((bias > stage ? bias : stage) + 15) & ~15;
 }
 
@@ -623,31 +699,27 @@ typedef _Float16 GlbTab;
 template <int D>
 size_t global_lds_bytes(int w)
 {
-    int ts = w | 1;
-    return (size_t)2 * GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)4 * wave_scratch_bytes<D>(ts, sizeof(GlbTab)) + (size_t)GLB_TILE * 4;
+    // K and V tile, the four waves' bias tables, per key (or per block) table offsets
+    return (size_t)2 * GLB_TILE * AttnCfg<D>::KSTR * 2 + (size_t)4 * wave_scratch_bytes<D>(glb_tstr(w)) + (size_t)GLB_TILE * 4;
 }
 
-template <int D>
-__global__ void __launch_bounds__(256, 2)
-attn_global_kernel(AttnParams P, int T, int n_gh)
+// Everything a workgroup of the global kernel does once it knows which way its scores are formed.
+// PATCHED: every block of every tile this workgroup visits is a patch (attn_chunk_step_patch: bias by MFMA);
+// otherwise the general path (per-key table look-ups, any order).
+template <int D, bool PATCHED>
+__device__ __forceinline__ void attn_global_body(const AttnParams &P, int qt, int grp, int head, float inv_scale, unsigned char *smem)
 {
     using C = AttnCfg<D>;
     constexpr int LOADS = GLB_TILE * C::CH / 256;       // 16-byte chunks per thread per operand
     static_assert(GLB_TILE * C::CH % 256 == 0, "tile chunks must divide over the workgroup");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int ts = P.w | 1;
+    const int tstr = glb_tstr(P.w);
     bf16 *Ks = reinterpret_cast<bf16 *>(smem);
     bf16 *Vs = Ks + GLB_TILE * C::KSTR;
     unsigned char *Tb = reinterpret_cast<unsigned char *>(Vs + GLB_TILE * C::KSTR);
-    const int wsb = wave_scratch_bytes<D>(ts, sizeof(GlbTab));
-    uint32_t *krc = reinterpret_cast<uint32_t *>(Tb + 4 * wsb);
+    const int wsb = wave_scratch_bytes<D>(tstr);
+    uint32_t *krc = reinterpret_cast<uint32_t *>(Tb + 4 * wsb);    // [128] per key (general) or [4] per block (patches)
 
-    // the query tiles of one (image, head) run on one XCD (workgroup b sits on XCD b & 7), whose L2 then
-    // serves the re-reads of that problem's K and V tiles
-    const int qt = (blockIdx.x >> 3) % T, gh = ((blockIdx.x >> 3) / T) * 8 + (blockIdx.x & 7);
-    if (gh >= n_gh) return;
-    const int grp = gh / P.h, head = gh % P.h;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int S = P.S;
     const long base = (long)grp * S * P.row_stride + (long)head * D;
 
@@ -663,26 +735,45 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
         if (P.out_rows) my_row = P.out_rows[my_row];
     }
     GlbTab *tq = reinterpret_cast<GlbTab *>(Tb + wave * wsb);
+    GlbTab *tq_lane = tq + l32 * tstr;            // this lane's query row of the wave's bias table
 
     constexpr int NB = glb_nb<D>();
     const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
     u32x4 rk[LOADS], rv[LOADS];
     int rcell = 0;
+    // this (image, head)'s K and V: a uniform base and 32-bit byte offsets (S * row_stride * 2 < 2^31, checked on the host)
+    const unsigned char *kbase = reinterpret_cast<const unsigned char *>(P.k + base);
+    const unsigned char *vbase = reinterpret_cast<const unsigned char *>(P.v + base);
+    const uint32_t rs2 = (uint32_t)P.row_stride * 2u;
+
+    // operand a of the bias product of patch blocks: lane (key l32, half) holds E[l32][8*half + e]
+    f16x8 efrag;
+    if constexpr (PATCHED) {
+        const int rr = patch_rr(l32), cc = patch_cc(l32);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int f = 8 * half + e;
+            efrag[e] = (_Float16)((f < 4 ? rr == f : (f < 12 ? cc == f - 4 : false)) ? 1.f : 0.f);
+        }
+    }
 
     // WHAT: 1 = K and the keys' cells, 2 = V; the two halves are requested at different points of the
-    // current tile's work so that the waves do not queue up behind each other's loads
+    // current tile's work so that the waves do not queue up behind each other's loads.  With patches only the
+    // first key of each block is looked up.
 #define ATTN_LOAD_TILE(kt_, WHAT)                                                                       \
     {                                                                                                   \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         const int key0_ = (kt_) * GLB_TILE;                                                             \
         _Pragma("unroll") for (int i = 0; i < LOADS; ++i)                                               \
         {                                                                                               \
-            int id = tid + i * 256, key = key0_ + id / C::CH, c = id % C::CH;                           \
-            key = key < S ? key : S - 1; /* keys past S repeat the last row; masked in the scores */   \
-            if ((WHAT) & 1) rk[i] = *reinterpret_cast<const u32x4 *>(P.k + base + (long)key * P.row_stride + c * 8); \
-            if ((WHAT) & 2) rv[i] = *reinterpret_cast<const u32x4 *>(P.v + base + (long)key * P.row_stride + c * 8); \
+            const int id = tid + i * 256, kl = id / C::CH, c = id - kl * C::CH;                         \
+            /* keys past S repeat the last row (masked in the scores); 32-bit byte offset from a uniform base */ \
+            const uint32_t off_ = (uint32_t)min(key0_ + kl, S - 1) * rs2 + (uint32_t)c * 16u;           \
+            if ((WHAT) & 1) rk[i] = *reinterpret_cast<const u32x4 *>(kbase + off_);                     \
+            if ((WHAT) & 2) rv[i] = *reinterpret_cast<const u32x4 *>(vbase + off_);                     \
         }                                                                                               \
-        if (((WHAT) & 1) && tid < GLB_TILE) rcell = sg[min(key0_ + tid, S - 1)]; /* used at the LDS store, not before */ \
+        if (((WHAT) & 1) && tid < (PATCHED ? GLB_TILE / 32 : GLB_TILE))                                 \
+            rcell = sg[min(key0_ + (PATCHED ? 32 * tid : tid), S - 1)]; /* used at the LDS store, not before */ \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
 #define ATTN_STORE_TILE()                                                                               \
@@ -693,12 +784,12 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
             *reinterpret_cast<u32x4 *>(Ks + key * C::KSTR + c * 8) = rk[i];                             \
             *reinterpret_cast<u32x4 *>(Vs + key * C::KSTR + c * 8) = rv[i];                             \
         }                                                                                               \
-        if (tid < GLB_TILE) krc[tid] = cell_bias_offsets(rcell, P.w, ts, sizeof(GlbTab));              \
+        if (tid < (PATCHED ? GLB_TILE / 32 : GLB_TILE)) krc[tid] = cell_bias_offsets(rcell, P.w);      \
     }
 
     ATTN_LOAD_TILE(0 < P.n_pre ? 0 : qt, 3)       // in flight while the bias rows are formed
     set_ones_columns<D>(Vs, GLB_TILE, tid, 256);
-    build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq, ts);
+    build_bias_rows<D, GlbTab>(qf, P.rel_h, P.rel_w, D, P.w, (int)(qrc & 0xffffu), (int)(qrc >> 16), tq_lane, inv_scale);
 
     WaveState<D> st;
     init_state<D>(st);
@@ -709,30 +800,102 @@ attn_global_kernel(AttnParams P, int T, int n_gh)
         LDS_BARRIER();
         const int kt_next = a + 1 < P.n_pre ? a + 1 : qt;
         if (a + 1 < nact) ATTN_LOAD_TILE(kt_next, NB < GLB_TILE / 32 ? 1 : 3)     // one step per tile: nothing to put V between
-        const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
         // the softmax / MFMA phase goes ahead of the other workgroup's tile traffic (loads, LDS stores, barriers)
         __builtin_amdgcn_s_setprio(1);
+        if constexpr (PATCHED) {
 #pragma unroll
-        for (int c0 = 0; c0 < GLB_TILE / 32; c0 += NB) {
-            if (c0 >= nblk) break;
-            int blk[NB], key0[NB];
+            for (int c0 = 0; c0 < GLB_TILE / 32; c0 += NB) {
+                int blk[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
-            const int nb = min(NB, nblk - c0);
-            const bool ragged = key0[NB - 1] + 32 > S;
-            if (ragged)
-                attn_chunk_step<D, NB, true, false, GlbTab, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
-            else
-                attn_chunk_step<D, NB, false, false, GlbTab, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq + l32, tq + l32);
-            if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
+                for (int b = 0; b < NB; ++b) blk[b] = c0 + b;
+                attn_chunk_step_patch<D, NB>(st, qf, Ks, Vs, krc, blk, efrag, reinterpret_cast<const unsigned char *>(tq_lane), P.scale_log2e);
+                if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
+            }
+        } else {
+            const int nblk = min(GLB_TILE / 32, (S - kt * GLB_TILE + 31) / 32);     // blocks wholly past the end are skipped
+#pragma unroll
+            for (int c0 = 0; c0 < GLB_TILE / 32; c0 += NB) {
+                if (c0 >= nblk) break;
+                int blk[NB], key0[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) { blk[b] = c0 + b; key0[b] = kt * GLB_TILE + 32 * (c0 + b); }
+                const int nb = min(NB, nblk - c0);
+                const bool ragged = key0[NB - 1] + 32 > S;
+                if (ragged)
+                    attn_chunk_step<D, NB, true, false, GlbTab, true, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq_lane, tq_lane);
+                else
+                    attn_chunk_step<D, NB, false, false, GlbTab, true, true>(st, qf, Ks, Vs, krc, blk, key0, nb, S, P.scale_log2e, tq_lane, tq_lane);
+                if (NB < GLB_TILE / 32 && c0 == 0 && a + 1 < nact) ATTN_LOAD_TILE(kt_next, 2)
+            }
         }
         __builtin_amdgcn_s_setprio(0);
     }
     finish_and_store<D>(st, reinterpret_cast<bf16 *>(tq), P.out + (long)head * D, (long)P.h * D, my_row);
+#undef ATTN_LOAD_TILE
+#undef ATTN_STORE_TILE
+}
+
+// TRY_PATCH: the instantiation for a shared position-only order on a power-of-two grid.  The workgroup first looks at
+// the cells of every key it will visit: if every 32-key block is a patch (see attn_chunk_step_patch) it forms the bias
+// with the matrix core, otherwise (any table is legal) it takes the general path.  !TRY_PATCH: the general path only.
+template <int D, bool TRY_PATCH>
+__global__ void __launch_bounds__(256, 2)
+attn_global_kernel(AttnParams P, int T, int n_gh, float inv_scale)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // the query tiles of one (image, head) run on one XCD (workgroup b sits on XCD b & 7), whose L2 then
+    // serves the re-reads of that problem's K and V tiles
+    const int qt = (blockIdx.x >> 3) % T, gh = ((blockIdx.x >> 3) / T) * 8 + (blockIdx.x & 7);
+    if (gh >= n_gh) return;
+    const int grp = gh / P.h, head = gh % P.h;
+    if constexpr (TRY_PATCH) {
+        // A key passes if it lies inside S, sits where the patch anchored at its block's first key puts it (inside the
+        // grid), and, for a block's first key, the block's 4 row and 8 column entries start at 8- and 16-byte
+        // boundaries of a table row.  256 consecutive keys a pass, the cells of a pass requested together.
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int32_t *sg = P.sigma + (long)grp * P.sigma_stride;
+        const int nact = P.n_pre + (qt >= P.n_pre ? 1 : 0);
+        int *flag = reinterpret_cast<int *>(smem);
+        if (tid == 0) *flag = 1;
+        bool ok = true;
+        constexpr int BATCH = 8;                                            // cells per thread per pass: 16 tiles a pass
+        for (int a = 0; a < nact; a += 2 * BATCH) {
+            int cell[BATCH], key[BATCH];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {                               // the loads of a pass are in flight together
+                const int a1 = min(a + 2 * j + (tid >> 7), nact - 1);       // this thread's tile (past the end: the last one again)
+                const int kt = a1 < P.n_pre ? a1 : qt;
+                key[j] = kt * GLB_TILE + (tid & 127);
+                cell[j] = sg[min(key[j], P.S - 1)];
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const int c0 = __shfl(cell[j], lane & 32, 64);              // cell of the block's first key
+                const int k = tid & 31, r0 = c0 / P.w, cl0 = c0 - r0 * P.w;
+                bool good = key[j] < P.S && c0 >= 0 && r0 + 6 < P.w && cl0 + 14 < P.w &&
+                            cell[j] == c0 + 2 * P.w * patch_rr(k) + 2 * patch_cc(k);
+                if (k == 0) {
+                    const uint32_t off = cell_bias_offsets(cell[j], P.w);
+                    good = good && (off & 7u) == 0 && ((off >> 16) & 15u) == 0;
+                }
+                ok = ok && good;
+            }
+        }
+        __syncthreads();
+        if (!ok) *flag = 0;
+        __syncthreads();
+        const bool patched = *flag != 0;
+        __syncthreads();                        // the flag's word is part of the K tile from here on
+        if (patched) {
+            attn_global_body<D, true>(P, qt, grp, head, inv_scale, smem);
+            return;
+        }
+    }
+    attn_global_body<D, false>(P, qt, grp, head, inv_scale, smem);
 }
 
 template <int D>
-int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_t st)
+int launch_attention(const AttnParams &P, int groups, int mask_block, float inv_scale, hipStream_t st)
 {
     if (mask_block == 32) {
         int nqb = ssam_div_up(P.S, 32);
@@ -755,11 +918,14 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, hipStream_
         int T = ssam_div_up(P.S, GLB_TILE);
         size_t lds = global_lds_bytes<D>(P.w);
         if (lds > 160 * 1024) return SSAM_EUNSUPPORTED;
-        auto kern = attn_global_kernel<D>;
+        // a shared table on a power-of-two grid of 16 x 16 or more can be the position-only order whose blocks are
+        // patches; the kernel checks every tile, so any table is still handled correctly
+        const bool patch = P.sigma_stride == 0 && P.w >= 16 && (P.w & (P.w - 1)) == 0;
+        auto kern = patch ? attn_global_kernel<D, true> : attn_global_kernel<D, false>;
         if (lds > 64 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return SSAM_EHIP;
-        hipLaunchKernelGGL(kern, dim3((unsigned)((long)T * ssam_div_up(groups * P.h, 8) * 8)), dim3(256), lds, st, P, T, groups * P.h);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((long)T * ssam_div_up(groups * P.h, 8) * 8)), dim3(256), lds, st, P, T, groups * P.h, inv_scale);
     }
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
@@ -784,6 +950,7 @@ extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v
         if (S > 224) return SSAM_EUNSUPPORTED;
     } else if (mask_block == 128) {
         if (S > 16384 || (long)ssam_div_up(S, 128) * ((long)groups * h + 7) > 0x7fffffffL) return SSAM_EUNSUPPORTED;
+        if ((long)S * row_stride * 2 > 0x7fffffffL) return SSAM_EUNSUPPORTED;      // the kernel's 32-bit byte offsets within a group
     } else {
         return SSAM_EUNSUPPORTED;
     }
@@ -799,12 +966,14 @@ extern "C" int ssam_sparse_attention(const void *q, const void *k, const void *v
     P.S = S; P.w = w; P.h = h;
     P.n_pre = ssam_prefix_tiles(ssam_div_up(S, mask_block), r);
     P.scale_log2e = scale * LOG2E;
+    if (!(scale > 0.f)) return SSAM_EINVAL;      // the global kernel's bias table holds bias / scale
+    const float inv_scale = 1.0f / scale;
     hipStream_t st = (hipStream_t)stream;
     switch (d) {
-    case 64: return launch_attention<64>(P, groups, mask_block, st);
-    case 80: return launch_attention<80>(P, groups, mask_block, st);
-    case 32: return launch_attention<32>(P, groups, mask_block, st);
-    case 16: return launch_attention<16>(P, groups, mask_block, st);
+    case 64: return launch_attention<64>(P, groups, mask_block, inv_scale, st);
+    case 80: return launch_attention<80>(P, groups, mask_block, inv_scale, st);
+    case 32: return launch_attention<32>(P, groups, mask_block, inv_scale, st);
+    case 16: return launch_attention<16>(P, groups, mask_block, inv_scale, st);
     default: return SSAM_EUNSUPPORTED;
     }
 }

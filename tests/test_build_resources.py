@@ -43,8 +43,9 @@ def test_hot_kernels_keep_their_register_budget():
     assert len(hot) >= 20, "expected every GEMM and attention instantiation in the record"
     for name, r in hot:
         assert r["spill"] == 0 and r["scratch"] == 0, (name, r)
-        # the row-major form of the 128x256 tile (forced choice only) keeps W in LDS, 96 KB a workgroup: it is alone
-        # on its CU with one wave per SIMD whatever its registers, so the two-waves budget does not apply to it
-        if "gemm_bf16_nt_kernelILi128ELi256E" in name and "ELb0E" in name:
+        # the row-major forms of the 128x256 and 256x128 tiles (forced choices only) keep both operands in LDS, 96 KB a
+        # workgroup: they are alone on their CU with one wave per SIMD whatever their registers, so the two-waves
+        # budget does not apply to them
+        if ("gemm_bf16_nt_kernelILi128ELi256E" in name or "gemm_bf16_nt_kernelILi256ELi128E" in name) and "ELb0E" in name:
             continue
         assert r["vgprs"] + r["agprs"] <= 256, (name, r)
