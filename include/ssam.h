@@ -402,6 +402,17 @@ int ssam_neck(const void *x, const void *w1, const float *ln1_g, const float *ln
               const void *w2, const float *ln2_g, const float *ln2_b, float eps, void *out,
               int B, int g, int D, int C, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Instrumentation for the benchmark's measured peaks (not part of the method) */
+/* ------------------------------------------------------------------------- */
+
+/* A loop of independent bf16 MFMAs on register operands (no memory traffic): `workgroups` workgroups of four
+ * waves, `iters` iterations of 8 x (32x32x16) (shape 0) or 16 x (16x16x32) (shape 1) MFMAs per wave; the caller
+ * times the launch.  ssam_probe_mfma_flops gives the flops of one launch.  sink dev fp32 [workgroups*256], written.
+ * SSAM_EINVAL on a bad shape, count or pointer. */
+double ssam_probe_mfma_flops(int workgroups, int iters);
+int ssam_probe_mfma(int shape, int workgroups, int iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

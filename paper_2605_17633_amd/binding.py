@@ -55,6 +55,7 @@ def lib():
                   "ssam_encoder_block_workspace_bytes", "ssam_encoder_workspace_bytes", "ssam_linear_workspace_bytes",
                   "ssam_patch_embed_workspace_bytes", "ssam_neck_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
+        L.ssam_probe_mfma_flops.restype = C.c_double
         _lib = L
     return _lib
 
@@ -499,3 +500,16 @@ def ssam_neck(x, w1, ln1_g, ln1_b, w2, ln2_g, ln2_b, g, eps=1e-6, out=None, work
         _f32(ln2_b, "ln2_b"), C.c_float(eps), _bf(out, "out"), C.c_int(Bn), C.c_int(g), C.c_int(D), C.c_int(Cn),
         C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
     return out
+
+
+# ------------------------------------------------------------------ instrumentation
+def ssam_probe_mfma_flops(workgroups: int, iters: int) -> float:
+    return float(lib().ssam_probe_mfma_flops(C.c_int(workgroups), C.c_int(iters)))
+
+
+def ssam_probe_mfma(shape: int, workgroups: int, iters: int, sink=None):
+    """Enqueue the MFMA-only loop (see the header); returns the flops of the launch.  The caller times it."""
+    if sink is None:
+        sink = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    _check("ssam_probe_mfma", lib().ssam_probe_mfma(C.c_int(shape), C.c_int(workgroups), C.c_int(iters), _f32(sink, "sink"), _stream()))
+    return ssam_probe_mfma_flops(workgroups, iters)

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssam.so")
-SOURCES = ["tables.hip", "movers.hip", "gemm.hip", "attention.hip", "block.hip", "ends.hip"]
+SOURCES = ["tables.hip", "movers.hip", "gemm.hip", "attention.hip", "block.hip", "ends.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
          "-Wno-inline-asm"]     # the window attention kernel names m0 in an asm clobber list (LDS-destination loads)
@@ -74,7 +74,7 @@ def _compile(src: str, obj: str):
     return _resources(p.stderr)
 
 
-def build_library(force: bool = True, jobs: int = 5) -> str:
+def build_library(force: bool = True, jobs: int = 6) -> str:
     """Compile every HIP source and link libssam.so.  Returns its path."""
     bdir = os.path.join(ROOT, "_build")
     os.makedirs(bdir, exist_ok=True)
