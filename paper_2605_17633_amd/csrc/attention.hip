@@ -894,13 +894,36 @@ attn_global_kernel(AttnParams P, int T, int n_gh, float inv_scale)
     attn_global_body<D, false>(P, qt, grp, head, inv_scale, smem);
 }
 
+// CU count and LDS bytes per CU of the current device, asked once per device (host-side queries, no allocation)
+struct DeviceShape { int cus; size_t lds; };
+inline int device_shape(DeviceShape &out)
+{
+    static DeviceShape cache[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SSAM_EHIP;
+    if (cache[dev].cus == 0) {
+        int cus = 0, lds = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return SSAM_EHIP;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess || lds <= 0) return SSAM_EHIP;
+        cache[dev].lds = (size_t)lds;
+        cache[dev].cus = cus;                    // written last: a racing first call finds 0 and asks again
+    }
+    out = cache[dev];
+    return SSAM_OK;
+}
+
 template <int D>
 int launch_attention(const AttnParams &P, int groups, int mask_block, float inv_scale, hipStream_t st)
 {
+    DeviceShape ds;
+    if (int rc = device_shape(ds); rc != SSAM_OK) return rc;
     if (mask_block == 32) {
         int nqb = ssam_div_up(P.S, 32);
         size_t lds = window_lds_bytes<D>(nqb, P.w);
-        if (lds > 160 * 1024) return SSAM_EUNSUPPORTED;
+        if (lds > ds.lds) return SSAM_EUNSUPPORTED;
+        // the queries of the next problem land in LDS through loads whose LDS address is a 16-bit immediate-free M0
+        // offset: their landing area is first in LDS and must end below 64 KB
+        if ((size_t)nqb * window_q_bytes<D>() > 64 * 1024) return SSAM_EUNSUPPORTED;
         auto kern = attn_window_kernel<D>;
         if (lds > 64 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -908,16 +931,16 @@ int launch_attention(const AttnParams &P, int groups, int mask_block, float inv_
         if (ssam_div_up((long)nqb * 32 * AttnCfg<D>::CH, nqb * 64) > WIN_MAX_LOADS) return SSAM_EUNSUPPORTED;
         if (2 * P.w - 1 > 32) return SSAM_EUNSUPPORTED;       // the window bias tables are one 32-row MFMA tile
         int n_problems = groups * P.h;
-        // persistent workgroups: as many as fit on the 256 CUs at once for this LDS footprint
-        int per_cu = (int)((160 * 1024) / lds);
+        // persistent workgroups: as many as fit on the device's CUs at once for this LDS footprint
+        int per_cu = (int)(ds.lds / lds);
         if (per_cu < 1) per_cu = 1;
         if (per_cu > 4) per_cu = 4;
-        int grid = n_problems < 256 * per_cu ? n_problems : 256 * per_cu;
+        int grid = n_problems < ds.cus * per_cu ? n_problems : ds.cus * per_cu;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(nqb * 64), lds, st, P, groups);
     } else {
         int T = ssam_div_up(P.S, GLB_TILE);
         size_t lds = global_lds_bytes<D>(P.w);
-        if (lds > 160 * 1024) return SSAM_EUNSUPPORTED;
+        if (lds > ds.lds) return SSAM_EUNSUPPORTED;
         // a shared table on a power-of-two grid of 16 x 16 or more can be the position-only order whose blocks are
         // patches; the kernel checks every tile, so any table is still handled correctly
         const bool patch = P.sigma_stride == 0 && P.w >= 16 && (P.w & (P.w - 1)) == 0;

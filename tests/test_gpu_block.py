@@ -98,6 +98,40 @@ def test_attention_output_row_map(w, Bm):
     assert bool((out[int(keep.sum()):] == 9.0).all())
 
 
+@pytest.mark.parametrize("w,d,r,how", [(64, 80, 0.4, "shuffled"), (32, 64, 0.5, "shuffled"), (64, 80, 0.4, "one swap, late tile"),
+                                       (64, 64, 0.3, "one swap, first tile"), (16, 32, 0.5, "rows and columns swapped")])
+def test_global_attention_shared_table_that_is_not_the_patch_order(w, d, r, how):
+    """A table shared by all groups on a power-of-two grid is first tried as the position-only Stripe-Sort order
+    (32-key blocks = 4 x 8 patches of stride 2, bias formed by the matrix core); every workgroup checks the cells
+    of the keys it visits and must take the general path when they are anything else.  Any bijection is a legal
+    order: a random one, the position-only one with two cells exchanged (only the workgroups that visit that tile
+    fall back), the position-only one transposed (every block is a patch of columns x rows: not the layout the
+    patch path assumes)."""
+    announce("global attention, odd shared table", w, d, r, how)
+    rng = np.random.default_rng(77 + w)
+    S, h, groups = w * w, 2, 2
+    sigma = B.ssam_build_perm(w, w, 4)[0].copy()
+    if how == "shuffled":
+        sigma = rng.permutation(S).astype(np.int32)
+    elif how == "one swap, late tile":
+        a, b_ = S - 5, S - 300                     # two keys of the last and third-last 128-key tiles
+        sigma[[a, b_]] = sigma[[b_, a]]
+    elif how == "one swap, first tile":
+        sigma[[3, 77]] = sigma[[77, 3]]            # inside the dense prefix: every workgroup visits it
+    else:
+        sigma = ((sigma % w) * w + sigma // w).astype(np.int32)
+    sinv = np.empty(S, np.int32)
+    sinv[sigma] = np.arange(S, dtype=np.int32)
+    q, k, v = (inputs.bf16_round(rng.normal(size=(groups, h, S, d)).astype(np.float32) * 0.7) for _ in range(3))
+    rel_h, rel_w = (inputs.bf16_round(rng.normal(size=(2 * w - 1, d)).astype(np.float32) * 0.3) for _ in range(2))
+    qkv = np.stack([q, k, v], axis=1).transpose(0, 3, 1, 2, 4)                 # [groups, S, 3, h, d] in SPATIAL order
+    out = B.ssam_sparse_attention(dev_bf16(np.ascontiguousarray(qkv[:, sigma])), dev_bf16(rel_h), dev_bf16(rel_w), dev_i32(sigma), w, 128, r)
+    got = to_np(out).reshape(groups, S, h, d)
+    for gi in range(groups):
+        ref = oracle.attention(q[gi], k[gi], v[gi], rel_h, rel_w, w, 4, 128, r, sinv=sinv)          # [h, S, d] spatial
+        assert_close(got[gi], ref.transpose(1, 0, 2)[sigma], f"global attention, {how}, group {gi}")
+
+
 def test_attention_plain_morton_order():
     announce("attention G=1")
     got, ref = run_attention_case(2, 14, 2, 64, 32, 0.4, G=1)
