@@ -56,6 +56,8 @@ def parse():
     ap.add_argument("--no-parts", action="store_true", help="skip the per-entry-point timings")
     ap.add_argument("--no-fold-ln1", action="store_true",
                     help="keep LN1 a pass of its own (by default it is folded into the qkv contraction)")
+    ap.add_argument("--no-fold-ln2", action="store_true",
+                    help="keep gather + LN2 a pass of its own (by default they are folded into fc1)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain row copy of known size (identity ssam_permute over the input batch), "
@@ -310,7 +312,13 @@ def time_parts(torch, np, hip, B, shape, g, Bn, r, K, x0, wts, wtab, wsig, gtab,
     w1p, w2p = B.ssam_pack_weight(w0["w1"]), B.ssam_pack_weight(w0["w2"])      # the form the encoder uses
     ms = run(lambda: B.ssam_routed_mlp_packed(xs, keep, w0["ln2_g"], w0["ln2_b"], 1e-6, w1p, w0["b1"], w2p, w0["b2"],
                                               workspace=ws_buf))
+    parts["routed_mlp_ln2_apart"] = mfma(ms, 4.0 * Bn * K * D * Dm)
+    # the form the encoder runs: gather and LN2 folded into fc1 (statistics of the kept rows, then fc1 on x itself)
+    Wf, colsum1, b1f = B.ssam_fold_ln_weight(w0["w1"], w0["b1"], w0["ln2_g"], w0["ln2_b"])
+    w1fp = B.ssam_pack_weight(Wf)
+    ms = run(lambda: B.ssam_routed_mlp_folded(xs, keep, 1e-6, w1fp, colsum1, b1f, w2p, w0["b2"], workspace=ws_buf))
     parts["routed_mlp"] = mfma(ms, 4.0 * Bn * K * D * Dm)
+    del Wf, w1fp
     # scores (one read of x) and keep-set selection (latency bound: microseconds, once per image for all blocks)
     ms = run(lambda: B.ssam_score_tokens(x0.view(Bn, g, g, D), scores=scores, workspace=ws_buf))
     parts["score_tokens"] = hbm(ms, 2.0 * Bn * n * D)
@@ -431,7 +439,7 @@ def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
     shape = inputs.SHAPES[name]
     g = 64
     n = g * g
-    wts = [B.pack_block_weights(w, fold_ln1=True, fold_kv_bias=True) for w in device_weights(torch, seed, shape, g, dev)]
+    wts = [B.pack_block_weights(w, fold_ln1=True, fold_kv_bias=True, fold_ln2=True) for w in device_weights(torch, seed, shape, g, dev)]
     structs = [B.block_weights_struct(w) for w in wts]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)
@@ -510,7 +518,8 @@ def main():
     x0 = torch.from_numpy(x_host.reshape(Bn, n, shape.D)).to(dev).to(torch.bfloat16).contiguous()
     wts = device_weights(torch, args.seed + 1, shape, g, dev)
     # the four Linear weights of every block go into MFMA fragment order once, at load time (ssam_pack_weight)
-    wts_packed = [B.pack_block_weights(w, fold_ln1=not args.no_fold_ln1, fold_kv_bias=not args.no_fold_ln1) for w in wts]
+    wts_packed = [B.pack_block_weights(w, fold_ln1=not args.no_fold_ln1, fold_kv_bias=not args.no_fold_ln1,
+                                       fold_ln2=not args.no_fold_ln2) for w in wts]
     structs = [B.block_weights_struct(w) for w in wts_packed]
     flags = [i in shape.global_blocks for i in range(shape.depth)]
     plan = B.EncoderPlan(structs, flags)

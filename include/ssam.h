@@ -290,6 +290,18 @@ int ssam_routed_mlp_packed(void *x, const int32_t *keep_idx, const float *ln_g, 
                            const void *w1p, const float *b1, const void *w2p, const float *b2,
                            int B, int N, int D, int Dm, int K,
                            void *workspace, size_t workspace_bytes, void *stream);
+/* The same with the gather of the kept tokens and LN2 folded into fc1 (Sec. 4.2:
+ * only the kept rows are read, where they lie in the residual stream; the
+ * normalised rows are never written): one pass over the kept rows takes their
+ * statistics, fc1 reads those rows of x itself and finishes the LayerNorm in its
+ * epilogue by the formula given with ssam_fold_ln_weight.  w1fp = packed Wf,
+ * colsum1, b1f = the outputs of ssam_fold_ln_weight(w1, b1, ln_g, ln_b); w2p =
+ * packed w2.  Same workspace and restrictions as ssam_routed_mlp_packed; an
+ * index outside [0,N) skips its row. */
+int ssam_routed_mlp_folded(void *x, const int32_t *keep_idx, float eps,
+                           const void *w1fp, const float *colsum1, const float *b1f, const void *w2p, const float *b2,
+                           int B, int N, int D, int Dm, int K,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Encoder block and stack                                                   */
@@ -321,6 +333,12 @@ typedef struct ssam_block_weights {     /* every pointer: dev */
                                            and values for every block, so a stack writes them once instead of once
                                            per block. */
     const float *bproj_folded;          /* [D] fp32 (fold_kv_bias only)              */
+    int fold_ln2;                       /* != 0 (needs packed != 0): the gather of the kept tokens and LN2 are folded
+                                           into fc1 (ssam_routed_mlp_folded): w1 is the packed form of the Wf that
+                                           ssam_fold_ln_weight makes from w1, b1, ln2_g, ln2_b; fc1_colsum and
+                                           b1_folded are its other outputs; b1, ln2_g, ln2_b are not read. */
+    const float *fc1_colsum;            /* [Dm] fp32 (fold_ln2 only)                 */
+    const float *b1_folded;             /* [Dm] fp32 (fold_ln2 only)                 */
 } ssam_block_weights;
 
 typedef struct ssam_block_cfg {

@@ -34,7 +34,8 @@ _WEIGHT_POINTERS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "rel_h", "rel_w", "wproj",
 class BlockWeights(C.Structure):
     _fields_ = ([(n, C.c_void_p) for n in _WEIGHT_POINTERS] + [("packed", C.c_int), ("fold_ln1", C.c_int),
                 ("qkv_colsum", C.c_void_p), ("bqkv_folded", C.c_void_p), ("fold_kv_bias", C.c_int),
-                ("bproj_folded", C.c_void_p)])
+                ("bproj_folded", C.c_void_p), ("fold_ln2", C.c_int), ("fc1_colsum", C.c_void_p),
+                ("b1_folded", C.c_void_p)])
 
 
 class BlockCfg(C.Structure):
@@ -293,6 +294,22 @@ def ssam_routed_mlp_packed(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, works
     return ssam_routed_mlp(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, workspace=workspace, w_packed=True)
 
 
+def ssam_routed_mlp_folded(x, keep_idx, eps, w1fp, colsum1, b1f, w2p, b2, workspace=None):
+    """Gather and LN2 folded into fc1: w1fp = ssam_pack_weight(Wf), (Wf, colsum1, b1f) = ssam_fold_ln_weight(w1, b1,
+    ln_g, ln_b); w2p = ssam_pack_weight(w2)."""
+    B, N, D = x.shape
+    Dm = w1fp.shape[0]
+    K = keep_idx.shape[1]
+    if workspace is None:
+        workspace = torch.empty(ssam_routed_mlp_workspace_bytes(B, K, D, Dm), dtype=torch.uint8, device=x.device)
+    _check("ssam_routed_mlp_folded", lib().ssam_routed_mlp_folded(
+        _bf(x, "x"), _i32(keep_idx, "keep_idx"), C.c_float(eps),
+        _bf(w1fp, "w1fp"), _f32(colsum1, "colsum1"), _f32(b1f, "b1f"), _bf(w2p, "w2p"), _f32(b2, "b2"),
+        C.c_int(B), C.c_int(N), C.c_int(D), C.c_int(Dm), C.c_int(K),
+        C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream()))
+    return x
+
+
 # ------------------------------------------------------------------ block / encoder
 _BF16_FIELDS = ("wqkv", "rel_h", "rel_w", "wproj", "w1", "w2")
 
@@ -358,10 +375,11 @@ def ssam_fold_kv_bias(bias_in, bqkv, wproj, bproj):
     return bias_out, bproj_out
 
 
-def pack_block_weights(wt: dict, fold_ln1=False, fold_kv_bias=False) -> dict:
+def pack_block_weights(wt: dict, fold_ln1=False, fold_kv_bias=False, fold_ln2=False) -> dict:
     """Device weight dict (row-major weights) -> the same with the four Linear weights in fragment order (flagged
     'packed').  fold_ln1: wqkv becomes the packed LN1-folded weight (ssam_fold_ln_weight), with its column sums
-    and bias; fold_kv_bias (with fold_ln1): the key and value biases move out of the contraction (ssam_fold_kv_bias)."""
+    and bias; fold_kv_bias (with fold_ln1): the key and value biases move out of the contraction (ssam_fold_kv_bias);
+    fold_ln2: w1 becomes the packed LN2-folded weight, with its column sums and bias."""
     out = dict(wt)
     for k in _PACKABLE:
         out[k] = ssam_pack_weight(wt[k])
@@ -375,16 +393,24 @@ def pack_block_weights(wt: dict, fold_ln1=False, fold_kv_bias=False) -> dict:
             out["fold_kv_bias"] = True
     elif fold_kv_bias:
         raise ValueError("fold_kv_bias needs fold_ln1")
+    if fold_ln2:
+        Wf, colsum, bias_f = ssam_fold_ln_weight(wt["w1"], wt["b1"], wt["ln2_g"], wt["ln2_b"])
+        out["w1"] = ssam_pack_weight(Wf)
+        out["fc1_colsum"], out["b1_folded"], out["fold_ln2"] = colsum, bias_f, True
     return out
 
 
-def upload_block_weights(wdict: dict, device="cuda", pack=False, fold_ln1=False, fold_kv_bias=False) -> dict:
+def upload_block_weights(wdict: dict, device="cuda", pack=False, fold_ln1=False, fold_kv_bias=False, fold_ln2=False) -> dict:
     """numpy fp32 dict (bf16-representable values) -> device tensors in the ABI's dtypes."""
     out = {}
     for k, v in wdict.items():
         t = torch.from_numpy(np.ascontiguousarray(v))
         out[k] = t.to(device=device, dtype=torch.bfloat16 if k in _BF16_FIELDS else torch.float32).contiguous()
-    return pack_block_weights(out, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias) if pack else out
+    if not pack:
+        if fold_ln2:
+            raise ValueError("fold_ln2 needs pack")
+        return out
+    return pack_block_weights(out, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias, fold_ln2=fold_ln2)
 
 
 def block_weights_struct(wt: dict) -> BlockWeights:
@@ -404,6 +430,11 @@ def block_weights_struct(wt: dict) -> BlockWeights:
     if s.fold_kv_bias:
         _dev(wt["bproj_folded"], torch.float32, "bproj_folded")
         s.bproj_folded = wt["bproj_folded"].data_ptr()
+    s.fold_ln2 = 1 if wt.get("fold_ln2") else 0
+    if s.fold_ln2:
+        for name in ("fc1_colsum", "b1_folded"):
+            _dev(wt[name], torch.float32, name)
+            setattr(s, name, wt[name].data_ptr())
     return s
 
 

@@ -17,6 +17,12 @@ int ssam_invert_table(const int32_t *table, int table_batch_stride, int B, int N
 int ssam_linear_ln_impl(const void *A, const float *stats, const void *Wfp, const float *colsum, const float *bias_f,
                         void *C, int M, int N, int K, const GemmLd &ld, const GemmRowMap &rm, hipStream_t st);
 
+int ssam_linear_fold_gelu_impl(const void *A, const int32_t *src, const float *stats, const void *Wfp, const float *colsum,
+                               const float *bias_f, void *C, int M, int N, int K, const GemmLd &ld,
+                               void *split_ws, size_t split_ws_bytes, hipStream_t st);
+int ssam_ln_stats_impl(const void *x, float *stats, long rows, int D, float eps, const int32_t *idx, int idx_batch_stride,
+                       int Nin, int Nout, int32_t *src, hipStream_t st);
+
 namespace {
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -99,12 +105,15 @@ extern "C" size_t ssam_routed_mlp_workspace_bytes(int B, int K, int D, int Dm)
     return mlp_ws_bytes(B, K, D, Dm);
 }
 
+// colsum1 != NULL: gather and LN2 folded into fc1 (w1 the packed folded weight, b1 the folded bias; ln_g, ln_b unused)
 static int routed_mlp_impl(void *x, const int32_t *keep_idx, const float *ln_g, const float *ln_b, float eps,
                            const void *w1, const float *b1, const void *w2, const float *b2, bool packed,
                            int B, int N, int D, int Dm, int K,
-                           void *workspace, size_t workspace_bytes, void *stream)
+                           void *workspace, size_t workspace_bytes, void *stream, const float *colsum1 = nullptr)
 {
-    if (!x || !keep_idx || !ln_g || !ln_b || !w1 || !b1 || !w2 || !b2 || !workspace) return SSAM_EINVAL;
+    const bool fold = colsum1 != nullptr;
+    if (!x || !keep_idx || (!fold && (!ln_g || !ln_b)) || !w1 || !b1 || !w2 || !b2 || !workspace) return SSAM_EINVAL;
+    if (fold && (!packed || !ssam_aligned16(colsum1) || !ssam_aligned16(b1))) return SSAM_EINVAL;
     if (B <= 0 || N <= 0 || D <= 0 || Dm <= 0 || K <= 0 || K > N) return SSAM_EINVAL;
     if (!ssam_aligned16(workspace)) return SSAM_EINVAL;
     if (D % 8 != 0 || Dm % 8 != 0) return SSAM_EUNSUPPORTED;
@@ -115,10 +124,20 @@ static int routed_mlp_impl(void *x, const int32_t *keep_idx, const float *ln_g, 
     void *hid = ws + align256((size_t)B * K * D * 2);
     void *split = ws + mlp_core_bytes(B, K, D, Dm);
     hipStream_t st = (hipStream_t)stream;
-    int rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
-    if (rc != SSAM_OK) return rc;
-    GemmRowMap none = { nullptr, 1, 0, 1 };
-    rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, packed, SSAM_EPI_BIAS_GELU, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
+    int rc;
+    if (fold) {
+        // the region of the normalised rows holds only their statistics and the rows of x they are (8 + 4 bytes a row)
+        float *stats = (float *)a2;
+        int32_t *src = (int32_t *)(stats + 2 * (size_t)B * K);
+        rc = ssam_ln_stats_impl(x, stats, (long)B * K, D, eps, keep_idx, K, N, K, src, st);
+        if (rc != SSAM_OK) return rc;
+        rc = ssam_linear_fold_gelu_impl(x, src, stats, w1, colsum1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, split, GEMM_SPLIT_WS_BYTES, st);
+    } else {
+        rc = ssam_ln_gather(x, keep_idx, K, ln_g, ln_b, eps, a2, B, N, K, D, stream);
+        if (rc != SSAM_OK) return rc;
+        GemmRowMap none = { nullptr, 1, 0, 1 };
+        rc = ssam_linear_impl(a2, w1, b1, hid, B * K, Dm, D, GemmLd{ D, D, Dm }, packed, SSAM_EPI_BIAS_GELU, none, 0, split, GEMM_SPLIT_WS_BYTES, st);
+    }
     if (rc != SSAM_OK) return rc;
     GemmRowMap scatter = { keep_idx, K, K, N };
     return ssam_linear_impl(hid, w2, b2, x, B * K, D, Dm, GemmLd{ Dm, Dm, D }, packed, SSAM_EPI_BIAS_SCATTER_ADD, scatter, 0,
@@ -139,6 +158,15 @@ extern "C" int ssam_routed_mlp_packed(void *x, const int32_t *keep_idx, const fl
                                       void *workspace, size_t workspace_bytes, void *stream)
 {
     return routed_mlp_impl(x, keep_idx, ln_g, ln_b, eps, w1p, b1, w2p, b2, true, B, N, D, Dm, K, workspace, workspace_bytes, stream);
+}
+
+extern "C" int ssam_routed_mlp_folded(void *x, const int32_t *keep_idx, float eps,
+                                      const void *w1fp, const float *colsum1, const float *b1f, const void *w2p, const float *b2,
+                                      int B, int N, int D, int Dm, int K,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!colsum1) return SSAM_EINVAL;
+    return routed_mlp_impl(x, keep_idx, nullptr, nullptr, eps, w1fp, b1f, w2p, b2, true, B, N, D, Dm, K, workspace, workspace_bytes, stream, colsum1);
 }
 
 // everything but the padding tables, which sit behind it (so that no step of either half overwrites them
@@ -271,6 +299,11 @@ static int encoder_block_impl(void *x, const ssam_block_weights *w, const ssam_b
         if (rc != SSAM_OK) return rc;
     }
     const size_t attn_bytes = attn_half_bytes(cfg, g);
+    if (w->fold_ln2 != 0) {
+        if (!packed || !w->fc1_colsum || !w->b1_folded) return SSAM_EINVAL;
+        return routed_mlp_impl(x, keep_idx, nullptr, nullptr, cfg->eps, w->w1, w->b1_folded, w->w2, w->b2, true,
+                               B, g.N, D, cfg->Dm, cfg->K, ws + attn_bytes, mlp_ws_bytes(B, cfg->K, D, cfg->Dm), stream, w->fc1_colsum);
+    }
     return routed_mlp_impl(x, keep_idx, w->ln2_g, w->ln2_b, cfg->eps, w->w1, w->b1, w->w2, w->b2, packed,
                            B, g.N, D, cfg->Dm, cfg->K, ws + attn_bytes, mlp_ws_bytes(B, cfg->K, D, cfg->Dm), stream);
 }

@@ -41,19 +41,20 @@ TailPlan plan_tail(int total, int slots, int nk, int subs, size_t sub_tile_bytes
     return p;
 }
 
-template <int BM, int BN, int EPI, int SUB_M, int SUB_N, int WGM = 2, int WGN = 2, bool WPACK = false>
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N, int WGM = 2, int WGN = 2, bool WPACK = false, bool LNF = false>
 int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
-                 const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm, const GemmSplit &sp, hipStream_t st)
+                 const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm, const GemmSplit &sp, const GemmFold &fold,
+                 hipStream_t st)
 {
     if (tr.tile_count <= 0) return SSAM_OK;
     constexpr size_t lds = gemm_lds_bytes<BM, BN, WGM, WGN, WPACK>();
-    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK>;
+    auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK, LNF>;
     // more than 64 KiB of LDS per workgroup needs the per-kernel opt-in (idempotent, host-side only)
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SSAM_EHIP;
     int per_xcd = ssam_div_up((long)tr.tile_count * SUB_M * SUB_N * sp.parts, 8);
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WGM * WGN), lds, st, A, W, bias, C, M, N, K, ld, tr, rm, sp);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * WGM * WGN), lds, st, A, W, bias, C, M, N, K, ld, tr, rm, sp, fold);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
 }
@@ -61,9 +62,9 @@ int launch_range(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
 // Whole rounds of BM x BN tiles, then the left-over tiles (when they would fill less than half a round)
 // as TM x TN tiles, BM = SUB_M*TM, BN = SUB_N*TN.  slots = workgroups the chip runs at once with the large
 // tile.  With a workspace, a long K and few left-over tiles, the left-over launch also cuts K (see the kernel).
-template <int BM, int BN, int TM, int TN, int EPI, int WGM = 2, int WGN = 2, bool WPACK = false>
+template <int BM, int BN, int TM, int TN, int EPI, int WGM = 2, int WGN = 2, bool WPACK = false, bool LNF = false>
 int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
-                 const GemmLd &ld, int slots, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
+                 const GemmLd &ld, int slots, const GemmRowMap &rm, const SplitWs &ws, const GemmFold &fold, hipStream_t st)
 {
     constexpr int SUB_M = BM / TM, SUB_N = BN / TN;
     const GemmSplit whole = { nullptr, 1 };
@@ -86,45 +87,47 @@ int launch_split(const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M
         static_assert(lds <= 64 * 1024, "the fused launch stays within the default LDS limit");
         if (parts > 1) {
             const GemmSplit sp = { (float *)ws.ptr, parts };
-            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, WPACK>),
-                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, sp, n_tail);
+            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, WPACK, LNF>),
+                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, sp, n_tail, fold);
             SSAM_CHECK_LAUNCH();
             constexpr int RPB = 256 / (TN / 8);
-            hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
-                               (const float *)ws.ptr, parts, bias, C, M, N, ld, tt, rm);
+            hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N, LNF>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
+                               (const float *)ws.ptr, parts, bias, C, M, N, ld, tt, rm, fold);
         } else {
-            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, EPI, SUB_M, SUB_N, WPACK>),
-                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, whole, n_tail);
+            hipLaunchKernelGGL((gemm_bf16_nt_fused_kernel<BM, BN, EPI, WGM, WGN, TM, TN, EPI, SUB_M, SUB_N, WPACK, LNF>),
+                               dim3(n_tail + n_main), dim3(256), lds, st, A, W, bias, C, M, N, K, ld, tr, tt, rm, whole, n_tail, fold);
         }
         SSAM_CHECK_LAUNCH();
         return SSAM_OK;
     }
-    int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    int rc = launch_range<BM, BN, EPI, 1, 1, WGM, WGN, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr, rm, whole, fold, st);
     if (rc != SSAM_OK || rem == 0) return rc;
     tr.tile_begin = total - rem;
     tr.tile_count = rem;
     const int n_sub = rem * SUB_M * SUB_N;
     if (parts > 1) {
         const GemmSplit sp = { (float *)ws.ptr, parts };
-        rc = launch_range<TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, sp, st);
+        rc = launch_range<TM, TN, GEMM_EPI_PARTIAL, SUB_M, SUB_N, 2, 2, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr, rm, sp, fold, st);
         if (rc != SSAM_OK) return rc;
         constexpr int RPB = 256 / (TN / 8);
-        hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
-                           (const float *)ws.ptr, parts, bias, C, M, N, ld, tr, rm);
+        hipLaunchKernelGGL((gemm_tail_reduce_kernel<TM, TN, EPI, SUB_M, SUB_N, LNF>), dim3(n_sub * (TM / RPB)), dim3(256), 0, st,
+                           (const float *)ws.ptr, parts, bias, C, M, N, ld, tr, rm, fold);
         SSAM_CHECK_LAUNCH();
         return SSAM_OK;
     }
-    return launch_range<TM, TN, EPI, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, whole, st);
+    return launch_range<TM, TN, EPI, SUB_M, SUB_N, 2, 2, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr, rm, whole, fold, st);
 }
 
-template <int EPI>
+const GemmFold no_fold = { nullptr, nullptr, nullptr };
+
+template <int EPI, bool LNF = false>
 int launch_tile_packed(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 *C, int M, int N, int K,
-                       const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
+                       const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st, const GemmFold &fold = no_fold)
 {
     switch (tile) {
-    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4, true>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
-    case 3: return launch_split<128, 128, 64, 128, EPI, 2, 2, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
-    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4, true>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
+    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4, true, LNF>(A, W, bias, C, M, N, K, ld, 256, rm, ws, fold, st);
+    case 3: return launch_split<128, 128, 64, 128, EPI, 2, 2, true, LNF>(A, W, bias, C, M, N, K, ld, 512, rm, ws, fold, st);
+    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4, true, LNF>(A, W, bias, C, M, N, K, ld, 512, rm, ws, fold, st);
     default: return SSAM_EUNSUPPORTED;
     }
 }
@@ -134,10 +137,10 @@ int launch_tile(int tile, const bf16 *A, const bf16 *W, const float *bias, bf16 
                 const GemmLd &ld, const GemmRowMap &rm, const SplitWs &ws, hipStream_t st)
 {
     switch (tile) {
-    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
-    case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, st);
-    case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);
-    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4>(A, W, bias, C, M, N, K, ld, 512, rm, ws, st);   // same plan as packed
+    case 1: return launch_split<256, 256, 128, 128, EPI, 2, 4>(A, W, bias, C, M, N, K, ld, 256, rm, ws, no_fold, st);
+    case 2: return launch_split<256, 128, 128, 128, EPI>(A, W, bias, C, M, N, K, ld, 256, rm, ws, no_fold, st);
+    case 3: return launch_split<128, 128, 64, 128, EPI>(A, W, bias, C, M, N, K, ld, 512, rm, ws, no_fold, st);
+    case 4: return launch_split<128, 256, 128, 128, EPI, 1, 4>(A, W, bias, C, M, N, K, ld, 512, rm, ws, no_fold, st);   // same plan as packed
     default: return SSAM_EINVAL;
     }
 }
@@ -206,6 +209,20 @@ int ssam_linear_impl(const void *A, const void *W, const float *bias, void *C, i
     }
 }
 
+// fc1 of the routed MLP with gather and LN2 folded in (see GemmFold): rows src[m] of A, packed folded weights,
+// GELU epilogue, any M; the tile is picked as for the plain contraction of the same shape.
+int ssam_linear_fold_gelu_impl(const void *A, const int32_t *src, const float *stats, const void *Wfp, const float *colsum,
+                               const float *bias_f, void *C, int M, int N, int K, const GemmLd &ld,
+                               void *split_ws, size_t split_ws_bytes, hipStream_t st)
+{
+    const SplitWs ws = { split_ws, split_ws_bytes };
+    const GemmFold fold = { reinterpret_cast<const float2 *>(stats), colsum, src };
+    const GemmRowMap none = { nullptr, 1, 0, 1 };
+    const int tile = pick_tile(M, N, K, SSAM_EPI_BIAS_GELU, ws, true);
+    return launch_tile_packed<SSAM_EPI_BIAS_GELU, true>(tile, (const bf16 *)A, (const bf16 *)Wfp, bias_f, (bf16 *)C, M, N, K, ld,
+                                                        none, ws, st, fold);
+}
+
 // The contraction with the LayerNorm of its A rows folded in (see GemmFold): 128x256 tiles, packed weights,
 // mapped store; M a multiple of 128 and N of 256, so there are no left-over tiles.
 int ssam_linear_ln_impl(const void *A, const float *stats, const void *Wfp, const float *colsum, const float *bias_f,
@@ -214,7 +231,7 @@ int ssam_linear_ln_impl(const void *A, const float *stats, const void *Wfp, cons
     constexpr size_t lds = gemm_lds_bytes<128, 256, 1, 4, true>();
     static_assert(lds <= 64 * 1024, "default LDS limit");
     GemmTileRange tr = { M / 128, N / 256, 0, (M / 128) * (N / 256) };
-    const GemmFold fold = { reinterpret_cast<const float2 *>(stats), colsum };
+    const GemmFold fold = { reinterpret_cast<const float2 *>(stats), colsum, nullptr };
     const int per_xcd = ssam_div_up(tr.tile_count, 8);
     hipLaunchKernelGGL((gemm_bf16_nt_lnf_kernel<128, 256, SSAM_EPI_BIAS_SCATTER, 1, 4>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16 *)A, (const bf16 *)Wfp, bias_f, (bf16 *)C, M, N, K, ld, tr, rm, fold);

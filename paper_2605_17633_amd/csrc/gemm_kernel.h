@@ -72,10 +72,12 @@ constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)32 << 20;   // workspace that let
 
 // LayerNorm folded into the contraction that follows it (LNF instantiations): A holds the rows before the
 // normalisation, W holds W*diag(gamma), and the epilogue finishes  rstd_m * (acc - mean_m * colsum_n) + bias_n
-// with bias_n = b_n + sum_k beta_k W[n][k].
+// with bias_n = b_n + sum_k beta_k W[n][k].  With `src` the rows are also gathered: row m of the product is row
+// src[m] of A (the routed MLP's kept tokens, read where they lie in the residual stream).
 struct GemmFold {
-    const float2 *stats;      // [M] per row of A: { rstd, -rstd * mean }
+    const float2 *stats;      // [M] per row of the product: { rstd, -rstd * mean } of the A row it reads
     const float *colsum;      // [N] sum over k of the folded weight as stored (bf16 values, fp32 sum)
+    const int32_t *src;       // [M] row of A per row of the product (all inside A), or NULL: row m itself
 };
 
 struct GemmSplit {
@@ -102,9 +104,11 @@ template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, in
 __device__ __forceinline__ void
 gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                   bf16 *C, int M, int N, int K, const GemmLd &ld, const GemmTileRange &tr, const GemmRowMap &rm,
-                  const GemmSplit &sp, int bid, const GemmFold &fold = GemmFold{ nullptr, nullptr })
+                  const GemmSplit &sp, int bid, const GemmFold &fold = GemmFold{ nullptr, nullptr, nullptr })
 {
-    static_assert(!LNF || EPI != GEMM_EPI_PARTIAL, "the folded LayerNorm is finished by the epilogue proper");
+    static_assert(!LNF || WPACK, "the folded forms exist for packed weights");
+    // a K range of a folded product only gathers its rows: the normalisation is finished where the ranges are added
+    constexpr bool FOLD_EPI = LNF && EPI != GEMM_EPI_PARTIAL;
     constexpr int THREADS = 64 * WGM * WGN, RSTEP = THREADS / 8;   // waves in a WGM x WGN grid; rows staged per pass
     constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32;       // MT: 32-row slices of the epilogue
     constexpr int MT16 = WM / 16, NT16 = WN / 16;                  // the wave's accumulator tiles (16x16)
@@ -154,8 +158,11 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     const int r0 = tid >> 3, c0 = tid & 7;
     const bf16 *ga[A_LOADS];
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i)          // rows past M repeat the last row; their results are never stored
-        ga[i] = A + (long)min(m0 + r0 + RSTEP * i, M - 1) * ld.a + c0 * 8;
+    for (int i = 0; i < A_LOADS; ++i) {        // rows past M repeat the last row; their results are never stored
+        long arow = min(m0 + r0 + RSTEP * i, M - 1);
+        if constexpr (LNF) if (fold.src) arow = fold.src[arow];
+        ga[i] = A + arow * ld.a + c0 * 8;
+    }
     const bf16 *gb[B_LOADS];
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i)          // likewise columns past N (a ragged last tile column)
@@ -351,8 +358,8 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     }
     const bool col_ok = ncol < N;               // N % 8 == 0: a lane's 8 columns are all inside or all outside
     constexpr int PASSES = 32 / RPP;
-    float sv[LNF ? 8 : 1];
-    if constexpr (LNF) {
+    float sv[FOLD_EPI ? 8 : 1];
+    if constexpr (FOLD_EPI) {
         const float4 *c4 = reinterpret_cast<const float4 *>(fold.colsum + (ncol < N ? ncol : 0));
         float4 x0 = c4[0], x1 = c4[1];
         sv[0] = x0.x; sv[1] = x0.y; sv[2] = x0.z; sv[3] = x0.w;
@@ -365,12 +372,12 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     int *dst_row = reinterpret_cast<int *>(reinterpret_cast<float *>(smem) + WGM * WGN * 32 * EPS);   // [BM], -1 = skip
     constexpr bool MAPPED = EPI == SSAM_EPI_BIAS_SCATTER_ADD || EPI == SSAM_EPI_BIAS_SCATTER;
     float2 *row_stats = reinterpret_cast<float2 *>(dst_row + BM);    // [BM] { rstd, -rstd*mean } (LNF), parked like dst_row
-    if (MAPPED || LNF) {
+    if (MAPPED || FOLD_EPI) {
         int mine = -1;
         float2 mine_stats = { 0.f, 0.f };
         if (tid < BM && m0 + tid < M) {
             int m = m0 + tid;
-            if constexpr (LNF) mine_stats = fold.stats[m];
+            if constexpr (FOLD_EPI) mine_stats = fold.stats[m];
             if (MAPPED) {
                 int b = m / rm.rows_per_batch, p = m - b * rm.rows_per_batch;
                 int idx = rm.map[(long)b * rm.map_batch_stride + p];
@@ -380,7 +387,7 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
         __syncthreads();                        // every wave is done with the pipeline buffers
         if (tid < BM) {
             if (MAPPED) dst_row[tid] = mine;
-            if constexpr (LNF) row_stats[tid] = mine_stats;
+            if constexpr (FOLD_EPI) row_stats[tid] = mine_stats;
         }
     }
     __syncthreads();                            // pipeline buffers free for staging; dst_row visible
@@ -389,7 +396,7 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     // stores of the passes before it, and every pass would then wait for the previous pass's store to complete.
 #pragma unroll
     for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(bv[e]));
-    if constexpr (LNF) {
+    if constexpr (FOLD_EPI) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(sv[e]));
     }
@@ -442,7 +449,7 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
                 continue;
             }
             float v[8] = { y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w };
-            if constexpr (LNF) {
+            if constexpr (FOLD_EPI) {
                 const float2 t = row_stats[wm + i * 32 + row];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = v[e] * t.x + (t.y * sv[e] + bv[e]);
@@ -475,12 +482,12 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
     }
 }
 
-template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false>
+template <int BM, int BN, int EPI, int SUB_M = 1, int SUB_N = 1, int WGM = 2, int WGN = 2, bool WPACK = false, bool LNF = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, (BN == 256 && WGM * WGN == 4 && WPACK) ? 2 : 1)
 gemm_bf16_nt_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
-                    bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp)
+                    bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmSplit sp, GemmFold fold)
 {
-    gemm_bf16_nt_body<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr, rm, sp, (int)blockIdx.x);
+    gemm_bf16_nt_body<BM, BN, EPI, SUB_M, SUB_N, WGM, WGN, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr, rm, sp, (int)blockIdx.x, fold);
 }
 
 // The same workgroup with the LayerNorm of its A rows folded in (see GemmFold).
@@ -498,27 +505,28 @@ gemm_bf16_nt_lnf_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, 
 // left-over sub-tiles (TEPI = the epilogue proper, or GEMM_EPI_PARTIAL with K ranges), the others the large
 // tiles.  The left-over workgroups are dispatched first and finish while the first round of large tiles runs,
 // instead of running as a launch of their own on a mostly idle chip.
-template <int BM, int BN, int EPI, int WGM, int WGN, int TM, int TN, int TEPI, int SUB_M, int SUB_N, bool WPACK>
+template <int BM, int BN, int EPI, int WGM, int WGN, int TM, int TN, int TEPI, int SUB_M, int SUB_N, bool WPACK, bool LNF = false>
 __global__ void __launch_bounds__(256, 2)
 gemm_bf16_nt_fused_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const float *__restrict__ bias,
                           bf16 *C, int M, int N, int K, GemmLd ld, GemmTileRange tr_main, GemmTileRange tr_tail,
-                          GemmRowMap rm, GemmSplit sp_tail, int n_tail)
+                          GemmRowMap rm, GemmSplit sp_tail, int n_tail, GemmFold fold)
 {
     static_assert(WGM * WGN == 4, "both kinds of workgroup are four waves");
     if ((int)blockIdx.x < n_tail) {
-        gemm_bf16_nt_body<TM, TN, TEPI, SUB_M, SUB_N, 2, 2, WPACK>(A, W, bias, C, M, N, K, ld, tr_tail, rm, sp_tail, (int)blockIdx.x);
+        gemm_bf16_nt_body<TM, TN, TEPI, SUB_M, SUB_N, 2, 2, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr_tail, rm, sp_tail, (int)blockIdx.x, fold);
     } else {
         const GemmSplit whole = { nullptr, 1 };
-        gemm_bf16_nt_body<BM, BN, EPI, 1, 1, WGM, WGN, WPACK>(A, W, bias, C, M, N, K, ld, tr_main, rm, whole, (int)blockIdx.x - n_tail);
+        gemm_bf16_nt_body<BM, BN, EPI, 1, 1, WGM, WGN, WPACK, LNF>(A, W, bias, C, M, N, K, ld, tr_main, rm, whole, (int)blockIdx.x - n_tail, fold);
     }
 }
 
 // Second half of a K-split left-over launch: adds the `parts` fp32 slots of every sub-tile in slot
-// order, then bias and the epilogue proper.  One thread finishes 8 consecutive columns of a row.
-template <int BM, int BN, int EPI, int SUB_M, int SUB_N>
+// order, then bias (with a folded LayerNorm: its row and column terms, see GemmFold) and the epilogue proper.
+// One thread finishes 8 consecutive columns of a row.
+template <int BM, int BN, int EPI, int SUB_M, int SUB_N, bool LNF = false>
 __global__ void __launch_bounds__(256)
 gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const float *__restrict__ bias, bf16 *C,
-                        int M, int N, GemmLd ld, GemmTileRange tr, GemmRowMap rm)
+                        int M, int N, GemmLd ld, GemmTileRange tr, GemmRowMap rm, GemmFold fold)
 {
     constexpr int LPR = BN / 8, RPB = 256 / LPR;                  // lanes per row, rows per workgroup
     constexpr int SUBS = SUB_M * SUB_N;
@@ -568,8 +576,17 @@ gemm_tail_reduce_kernel(const float *__restrict__ partial, int parts, const floa
         acc[0] += y0.x; acc[1] += y0.y; acc[2] += y0.z; acc[3] += y0.w;
         acc[4] += y1.x; acc[5] += y1.y; acc[6] += y1.z; acc[7] += y1.w;
     }
+    if constexpr (LNF) {
+        const float2 t = fold.stats[m];
+        const float4 *c4 = reinterpret_cast<const float4 *>(fold.colsum + ncol);
+        const float4 x0 = c4[0], x1 = c4[1];
+        const float cs[8] = { x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w };
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += acc[e];
+        for (int e = 0; e < 8; ++e) v[e] = acc[e] * t.x + (t.y * cs[e] + v[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += acc[e];
+    }
     if (EPI == SSAM_EPI_BIAS_GELU) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);

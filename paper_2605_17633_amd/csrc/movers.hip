@@ -127,14 +127,27 @@ ln_gather_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx, i
 // ---------------------------------------------------------------- LN statistics only
 // The statistics half of the LayerNorm above, for a contraction that has the normalisation folded in:
 // one wave per row, stats[row] = { rstd, -rstd * mean } (same two-pass fp32 arithmetic as ln_gather_kernel).
+// With `idx` (the kept tokens of the routed MLP, [B][idx_batch_stride] positions inside an image of Nin rows) the
+// statistics are those of the gathered rows, Nout per image, and src[row] receives the row of x that was read, for
+// the contraction that gathers the same rows; an index outside [0, Nin) reads the image's first row (its result is
+// dropped by the scatter that follows).
 template <int MAXC>
 __global__ void __launch_bounds__(256)
-ln_stats_kernel(const uint4 *__restrict__ x, float2 *__restrict__ stats, long rows, int chunks, float eps)
+ln_stats_kernel(const uint4 *__restrict__ x, float2 *__restrict__ stats, long rows, int chunks, float eps,
+                const int32_t *__restrict__ idx, int idx_batch_stride, int Nin, int Nout, int32_t *__restrict__ src)
 {
     int lane = threadIdx.x & 63;
     long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const uint4 *xrow = x + row * chunks;
+    long xr = row;
+    if (idx) {
+        const int b = (int)(row / Nout), p = (int)(row - (long)b * Nout);
+        int t = idx[(long)b * idx_batch_stride + p];
+        if (t < 0 || t >= Nin) t = 0;
+        xr = (long)b * Nin + t;
+        if (lane == 0) src[row] = (int32_t)xr;
+    }
+    const uint4 *xrow = x + xr * chunks;
     uint4 raw[MAXC];
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) raw[i] = xrow[min(lane + 64 * i, chunks - 1)];
@@ -640,22 +653,29 @@ int ssam_fill_bias_rows(void *C, long ldc, const float *bias, int n_cols, const 
     return SSAM_OK;
 }
 
-extern "C" int ssam_ln_stats(const void *x, float *stats, long rows, int D, float eps, void *stream)
+// statistics of rows idx[b][p] of image b (idx == NULL: of every row in order), see ln_stats_kernel
+int ssam_ln_stats_impl(const void *x, float *stats, long rows, int D, float eps, const int32_t *idx, int idx_batch_stride,
+                       int Nin, int Nout, int32_t *src, hipStream_t st)
 {
     if (!x || !stats || rows <= 0 || D <= 0 || D % 8 != 0) return SSAM_EINVAL;
     if (!ssam_aligned16(x) || ((uintptr_t)stats & 7)) return SSAM_EINVAL;
+    if (idx && (!src || Nin <= 0 || Nout <= 0 || (long)(rows / Nout) * Nin > 0x7fffffffL)) return SSAM_EINVAL;
     if (D > 2048) return SSAM_EUNSUPPORTED;
     int chunks = D / 8;
     dim3 grid((unsigned)ssam_div_up(rows, 4)), block(256);
-    hipStream_t st = (hipStream_t)stream;
     if (chunks <= 128)
-        hipLaunchKernelGGL(ln_stats_kernel<2>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+        hipLaunchKernelGGL(ln_stats_kernel<2>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps, idx, idx_batch_stride, Nin, Nout, src);
     else if (chunks <= 192)
-        hipLaunchKernelGGL(ln_stats_kernel<3>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+        hipLaunchKernelGGL(ln_stats_kernel<3>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps, idx, idx_batch_stride, Nin, Nout, src);
     else
-        hipLaunchKernelGGL(ln_stats_kernel<4>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps);
+        hipLaunchKernelGGL(ln_stats_kernel<4>, grid, block, 0, st, (const uint4 *)x, (float2 *)stats, rows, chunks, eps, idx, idx_batch_stride, Nin, Nout, src);
     SSAM_CHECK_LAUNCH();
     return SSAM_OK;
+}
+
+extern "C" int ssam_ln_stats(const void *x, float *stats, long rows, int D, float eps, void *stream)
+{
+    return ssam_ln_stats_impl(x, stats, rows, D, eps, nullptr, 0, 0, 0, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int ssam_fold_ln_weight(const void *W, int ldw, const float *bias, const float *gamma, const float *beta,

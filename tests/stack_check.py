@@ -51,7 +51,7 @@ def library_tables(g, ws, G=4):
 
 def check_stack(name, shape, g, x, wts, r, rho, variants, img=0, content_order=False, forced_blocks=None):
     """x [B,g,g,D] (bf16-representable fp32), wts: one numpy weight dict per block.
-    variants: list of (label, dict(pack=, fold_ln1=, fold_kv_bias=)); the first one also runs the
+    variants: list of (label, dict(pack=, fold_ln1=, fold_kv_bias=, fold_ln2=)); the first one also runs the
     composition check and the drift report.  forced_blocks: indices of the blocks checked teacher-forced
     (default: all).  Returns {label: worst teacher-forced max-rel error}."""
     B_, n, depth = x.shape[0], g * g, len(wts)
@@ -77,8 +77,8 @@ def check_stack(name, shape, g, x, wts, r, rho, variants, img=0, content_order=F
 
     def structs_for(opts):
         if opts.get("pack") or opts.get("fold_ln1"):
-            held = [B.pack_block_weights(w, fold_ln1=opts.get("fold_ln1", False), fold_kv_bias=opts.get("fold_kv_bias", False))
-                    for w in base]
+            held = [B.pack_block_weights(w, fold_ln1=opts.get("fold_ln1", False), fold_kv_bias=opts.get("fold_kv_bias", False),
+                                         fold_ln2=opts.get("fold_ln2", False)) for w in base]
         else:
             held = base
         return held, [B.block_weights_struct(w) for w in held]            # `held` keeps the tensors alive

@@ -161,7 +161,12 @@ def test_routed_mlp(B_, n, D, Dm, rho):
     wt = inputs.block_weights(rng, D, D // 64, Dm, 14)
     for kname in ("w1", "w2"):                                      # make the update comparable to x
         wt[kname] = inputs.bf16_round(wt[kname] * 4)
-    x = inputs.bf16_round(rng.normal(size=(B_, n, D)).astype(np.float32))
+    # LayerNorm parameters away from (1, 0), a bias that shows when dropped, rows with a mean of their own (the
+    # folded form subtracts mean * column sum after the contraction)
+    wt["ln2_g"] = (1.0 + 0.3 * rng.normal(size=D)).astype(np.float32)
+    wt["ln2_b"] = (0.2 * rng.normal(size=D)).astype(np.float32)
+    wt["b1"] = (0.3 * rng.normal(size=Dm)).astype(np.float32)
+    x = inputs.bf16_round((rng.normal(size=(B_, n, D)) + 0.7 * rng.normal(size=(B_, n, 1))).astype(np.float32))
     K = oracle.keep_count(n, rho)
     scores = inputs.lognormal_scores(rng, B_, n)
     keep = np.stack([oracle.select_tokens(scores[b], K) for b in range(B_)])
@@ -188,6 +193,17 @@ def test_routed_mlp(B_, n, D, Dm, rho):
             assert np.array_equal(gotp[b][rest].view(np.uint32), x[b][rest].view(np.uint32))
             assert_close(gotp[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"packed mlp delta b={b}",
                          stored=ref[keep[b]])
+        # gather and LN2 folded into fc1 (ssam_routed_mlp_folded): same bar, same bypass
+        Wf, colsum1, b1f = B.ssam_fold_ln_weight(wd["w1"], wd["b1"], wd["ln2_g"], wd["ln2_b"])
+        xf = dev_bf16(x)
+        B.ssam_routed_mlp_folded(xf, dev_i32(keep), 1e-6, B.ssam_pack_weight(Wf), colsum1, b1f, B.ssam_pack_weight(wd["w2"]), wd["b2"])
+        gotf = to_np(xf)
+        for b in range(B_):
+            ref = oracle.routed_mlp(x[b], keep[b], wt["ln2_g"], wt["ln2_b"], wt["w1"], wt["b1"], wt["w2"], wt["b2"])
+            rest = np.setdiff1d(np.arange(n), keep[b])
+            assert np.array_equal(gotf[b][rest].view(np.uint32), x[b][rest].view(np.uint32))
+            assert_close(gotf[b][keep[b]] - x[b][keep[b]], ref[keep[b]] - x[b][keep[b]], f"folded mlp delta b={b}",
+                         stored=ref[keep[b]])
     else:
         with pytest.raises(B.SsamError) as e:
             B.ssam_routed_mlp_packed(dev_bf16(x), dev_i32(keep), wd["ln2_g"], wd["ln2_b"], 1e-6, wd["w1"], wd["b1"], wd["w2"], wd["b2"])
@@ -209,10 +225,10 @@ def make_block_case(seed, B_, g, shape, ws, rho, scale_w=1.0):
     return wt, x, keep, K
 
 
-def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4, fold_ln1=False, fold_kv_bias=False):
+def run_block_gpu(wt, x, keep, shape, ws, Bm, r, G=4, fold_ln1=False, fold_kv_bias=False, fold_ln2=False):
     B_, g = x.shape[0], x.shape[1]
     n = g * g
-    wd = B.upload_block_weights(wt, pack=fold_ln1, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias)
+    wd = B.upload_block_weights(wt, pack=fold_ln1 or fold_ln2, fold_ln1=fold_ln1, fold_kv_bias=fold_kv_bias, fold_ln2=fold_ln2)
     cfg = B.make_cfg(B_, g, shape.D, shape.heads, shape.Dm, ws, Bm, keep.shape[1], r)
     if ws > 0:                                  # the library's own tables (the oracle's serve the reference side only)
         table = dev_i32(B.ssam_build_window_table(g, ws, G))
@@ -282,6 +298,28 @@ def test_encoder_block_folded_ln1(name, ws, Bm, shape_name):
         for b in range(x.shape[0]):
             assert_close(got[b] - x[b], refs[b] - x[b], f"folded LN1 (kv bias moved: {kv}), {name}: block delta b={b}",
                          stored=(x[b], mids[b], refs[b]), updates=2)
+
+
+@pytest.mark.parametrize("name,g,ws,Bm,rho", [("windowed with padding", 20, 14, 32, 0.3), ("global", 28, 0, 128, 0.4)])
+def test_encoder_block_folded_ln2(name, g, ws, Bm, rho):
+    """The gather of the kept tokens and LN2 folded into fc1 inside the block (LN1 not folded: these grids have no
+    folded qkv form), against the oracle's block to the bar of the plain path; rows outside the keep-set are
+    written by the attention half only."""
+    announce("encoder_block folded LN2", name)
+    shape = inputs.VIT_B
+    wt, x, keep, K = make_block_case(36, 2, g, shape, ws, rho)
+    rng = np.random.default_rng(37)
+    wt["ln2_g"] = (1.0 + 0.3 * rng.normal(size=shape.D)).astype(np.float32)
+    wt["ln2_b"] = (0.2 * rng.normal(size=shape.D)).astype(np.float32)
+    wt["b1"] = (0.3 * rng.normal(size=shape.Dm)).astype(np.float32)
+    ow = oracle.BlockWeights(**wt)
+    got, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4, fold_ln2=True)
+    plain, _ = run_block_gpu(wt, x, keep, shape, ws, Bm, 0.4)
+    for b in range(x.shape[0]):
+        mid, ref = oracle.encoder_block_halves(x[b], ow, shape.heads, ws, 4, Bm, 0.4, keep[b])
+        assert_close(got[b] - x[b], ref - x[b], f"folded LN2, {name}: block delta b={b}", stored=(x[b], mid, ref), updates=2)
+        rest = np.setdiff1d(np.arange(g * g), keep[b])
+        assert np.array_equal(got[b].reshape(g * g, -1)[rest].view(np.uint32), plain[b].reshape(g * g, -1)[rest].view(np.uint32))
 
 
 def test_encoder_block_folded_ln1_unsupported():

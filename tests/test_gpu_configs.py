@@ -34,7 +34,7 @@ def test_encoder_full_depth_batch1(model, r):
     x = inputs.token_field(np.random.default_rng(11), 1, G, shape.D)
     wts = inputs.encoder_weights(12, shape, G)
     check_stack(f"{model} encoder r={r}", shape, G, x, wts, r, r,
-                [("packed, LN1 and k/v biases folded", dict(pack=True, fold_ln1=True, fold_kv_bias=True)), ("row-major", dict())])
+                [("packed, LN1, k/v biases and LN2 folded", dict(pack=True, fold_ln1=True, fold_kv_bias=True, fold_ln2=True)), ("row-major", dict())])
 
 
 @pytest.mark.parametrize("r", [0.2, 0.3, 0.4, 0.6, 1.0])
@@ -98,3 +98,16 @@ def test_routed_mlp_batch16(rho):
                      stored=ref[sample])
     touched = np.abs(got - x).max(axis=2) > 0
     assert np.all(touched.sum(axis=1) <= K)
+    # the form the encoder runs: packed weights, gather and LN2 folded into fc1
+    Wf, colsum1, b1f = B.ssam_fold_ln_weight(wd["w1"], wd["b1"], wd["ln2_g"], wd["ln2_b"])
+    xf = dev_bf16(x)
+    B.ssam_routed_mlp_folded(xf, keep, 1e-6, B.ssam_pack_weight(Wf), colsum1, b1f, B.ssam_pack_weight(wd["w2"]), wd["b2"])
+    torch.cuda.synchronize()
+    gotf = to_np(xf)
+    for b in (0, 9):
+        rest = np.setdiff1d(np.arange(n), keep_np[b])
+        assert np.array_equal(gotf[b][rest].view(np.uint32), x[b][rest].view(np.uint32))
+        sample = np.sort(rng.choice(keep_np[b], size=96, replace=False)).astype(np.int32)
+        ref = oracle.routed_mlp(x[b], sample, wt["ln2_g"], wt["ln2_b"], wt["w1"], wt["b1"], wt["w2"], wt["b2"])
+        assert_close(gotf[b][sample] - x[b][sample], ref[sample] - x[b][sample], f"folded routed mlp rho={rho} image {b}",
+                     stored=ref[sample])

@@ -46,13 +46,13 @@ def test_vit_h_block_full_size(ws, Bm, img, R):
     got = to_np(xd[img]).reshape(G, G, SHAPE.D)
     mid, ref = oracle.encoder_block_halves(x[img], oracle.BlockWeights(**wt), SHAPE.heads, ws, 4, Bm, R, keep_gpu[img])
     assert_close(got - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} r={R} image {img}", stored=(x[img], mid, ref), updates=2)
-    # the same block with packed weights and LN1 folded into the qkv contraction (the form bench.py times)
+    # the same block with packed weights, LN1 folded into the qkv contraction and LN2 into fc1 (the form bench.py times)
     xf = torch.from_numpy(x.reshape(BATCH, n, SHAPE.D)).to(DEV).to(torch.bfloat16).contiguous()
-    wf = B.pack_block_weights(wd, fold_ln1=True, fold_kv_bias=True)
+    wf = B.pack_block_weights(wd, fold_ln1=True, fold_kv_bias=True, fold_ln2=True)
     B.ssam_encoder_block(xf, B.block_weights_struct(wf), cfg, table, sigma, keep)
     torch.cuda.synchronize()
     gotf = to_np(xf[img]).reshape(G, G, SHAPE.D)
-    assert_close(gotf - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} r={R} image {img}, folded LN1", stored=(x[img], mid, ref), updates=2)
+    assert_close(gotf - x[img], ref - x[img], f"ViT-H B=8 block ws={ws} r={R} image {img}, folded", stored=(x[img], mid, ref), updates=2)
     del xf
     # every image was processed: finite and changed; rows outside an image's keep-set were written once (by the
     # attention half) and rows inside it twice
@@ -64,10 +64,10 @@ def test_vit_h_block_full_size(ws, Bm, img, R):
 def test_vit_h_encoder_full_depth():
     """All 32 blocks at B = 8, density 0.4: ssam_encoder_forward against the loop of blocks bit for bit; every
     block of image 0 teacher-forced against the oracle at the 2e-2 bar, in the form bench.py times (packed
-    weights, LN1 and the key / value biases folded) and with plain row-major weights; drift of the free-running
+    weights; LN1, the key / value biases and LN2 folded) and with plain row-major weights; drift of the free-running
     stack reported apart.  (About a minute of oracle time on 16 cores.)"""
     rng = np.random.default_rng(7)
     x = inputs.token_field(rng, BATCH, G, SHAPE.D)
     wts = inputs.encoder_weights(8, SHAPE, G)
     check_stack("ViT-H B=8 encoder r=0.4", SHAPE, G, x, wts, 0.4, 0.4,
-                [("packed, LN1 and k/v biases folded", dict(pack=True, fold_ln1=True, fold_kv_bias=True)), ("row-major", dict())])
+                [("packed, LN1, k/v biases and LN2 folded", dict(pack=True, fold_ln1=True, fold_kv_bias=True, fold_ln2=True)), ("row-major", dict())])
