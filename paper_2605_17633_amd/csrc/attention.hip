@@ -505,15 +505,19 @@ inline int window_rel_rows(int w) { return ((2 * w - 1 + 31) / 32) * 32; }
 template <int D>
 __host__ __device__ constexpr int window_q_bytes() { return AttnCfg<D>::KS * 1024; }
 
+// LDS of a gfx950 compute unit.  A compile-time layout choice below is made for it; the launch itself checks the
+// size the device reports.
+constexpr long GFX950_LDS_BYTES = 160 * 1024;
+
 // Row stride of the output staging tile: padded like the K and V rows (conflict-free 8-byte stores) when a
-// 7-tile window then still fits the 160 KB of LDS, else the bare D (d = 80).
+// 7-tile window then still fits the LDS, else the bare D (d = 80).
 template <int D>
 __host__ __device__ constexpr int window_stage_stride()
 {
     constexpr int KSTR = AttnCfg<D>::KSTR, bias = 2 * 32 * WIN_TSTR * (int)sizeof(WinTab), stage = 32 * KSTR * 2;
     constexpr long total = 7L * window_q_bytes<D>() + 2L * 224 * KSTR * 2 + 2L * 32 * KSTR * 2 +
                            7L * (bias > stage ? bias : stage) + 224 * 4;
-    return total <= 160 * 1024 ? KSTR : D;
+    return total <= GFX950_LDS_BYTES ? KSTR : D;
 }
 
 template <int D>

@@ -83,6 +83,8 @@ def test_error_codes():
     assert L.ssam_select_tokens(None, None, 1, 8, 4, None) == B.EINVAL
     assert L.ssam_build_content_tables(None, 1, 8, 4, 4, None, None, None) == B.EINVAL
     assert L.ssam_pack_weight(None, 64, None, 32, 64, None) == B.EINVAL
+    assert L.ssam_routed_mlp_folded(None, None, C.c_float(1e-6), None, None, None, None, None, 1, 64, 128, 256, 16,
+                                    None, C.c_size_t(0), None) == B.EINVAL
     assert L.ssam_probe_mfma(0, 4, 10, None, None) == B.EINVAL and L.ssam_probe_mfma(2, 4, 10, buf, None) == B.EINVAL
     assert B.ssam_probe_mfma_flops(2, 3) == 2 * 4 * 3 * 8 * 2.0 * 32 * 32 * 16
     assert L.ssam_sparse_attention(None, None, None, C.c_long(0), None, None, None, C.c_long(0), None, None,
