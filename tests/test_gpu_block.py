@@ -344,7 +344,8 @@ def test_encoder_block_vit_h_dims():
 
 
 # ------------------------------------------------------------------ block stack
-@pytest.mark.parametrize("label,opts", [("row-major weights", dict()), ("packed weights", dict(pack=True))])
+@pytest.mark.parametrize("label,opts", [("row-major weights", dict()), ("packed weights", dict(pack=True)),
+                                        ("packed weights, LN2 folded", dict(pack=True, fold_ln2=True))])
 def test_encoder_forward_small_stack(label, opts):
     """3 blocks (the last one global) at ViT-B width on a 28x28 grid, two images: scores, keep-set and every
     block through ssam_encoder_forward: composition bit for bit, every block teacher-forced against the
@@ -416,7 +417,7 @@ def test_encoder_stack_content_order(depth, g):
         for kname in ("wqkv", "rel_h", "rel_w"):
             wt[kname] = inputs.bf16_round(wt[kname] * 4)               # peakier softmax: the mask matters
     x = inputs.token_field(np.random.default_rng(71), B_, g, shape.D)
-    opts = dict(pack=True) if depth == 3 else dict()
+    opts = dict(pack=True, fold_ln2=True) if depth == 3 else dict()
     for img in range(B_):
         check_stack(f"content-order stack, image {img}", shape, g, x, wts, r, rho, [("content order", opts)], img=img,
                     content_order=True)
