@@ -199,6 +199,26 @@ def measured_peaks(torch, hip, B, x0, shape, Bn, n):
     ms = timed(lambda: torch.matmul(A, W.t(), out=Cm), 100)
     out["vendor_library_qkv_tflops"] = round(2.0 * Bn * n * shape.D * 3 * shape.D / (ms * 1e-3) / 1e12, 1)
     out["vendor_library_note"] = "torch.matmul (hipBLASLt) on M x 3D x D, no bias, plain store; 100 back-to-back calls"
+    del A, W, Cm
+    # the four contraction shapes of a block, like for like: this library's kernel with packed weights and the plain
+    # bias epilogue against the vendor library's plain product (no bias); each 100 back-to-back calls
+    K_ = B.ssam_keep_count(n, 0.4)
+    by_shape = {}
+    ws_lin = torch.empty(B.ssam_linear_workspace_bytes(), dtype=torch.uint8, device=dev)
+    for name, (M_, N_, Kd) in (("qkv", (Bn * n, 3 * shape.D, shape.D)), ("proj", (Bn * n, shape.D, shape.D)),
+                               ("fc1", (Bn * K_, shape.Dm, shape.D)), ("fc2", (Bn * K_, shape.D, shape.Dm))):
+        A = torch.randn((M_, Kd), device=dev).to(torch.bfloat16)
+        W = (torch.randn((N_, Kd), device=dev) * 0.02).to(torch.bfloat16)
+        Wp = B.ssam_pack_weight(W)
+        bias = torch.zeros(N_, dtype=torch.float32, device=dev)
+        Cm = torch.empty((M_, N_), dtype=torch.bfloat16, device=dev)
+        fl = 2.0 * M_ * N_ * Kd
+        ms_v = timed(lambda: torch.matmul(A, W.t(), out=Cm), 100)
+        ms_o = timed(lambda: B.ssam_linear_ld(A, Wp, bias, Cm, workspace=ws_lin, w_packed=True), 100)
+        by_shape[name] = {"shape": [M_, N_, Kd], "ours_tflops": round(fl / (ms_o * 1e-3) / 1e12, 1),
+                          "vendor_library_tflops": round(fl / (ms_v * 1e-3) / 1e12, 1), "ratio": round(ms_v / ms_o, 3)}
+        del A, W, Wp, Cm
+    out["contractions_vs_vendor_library"] = by_shape
     out["mfma_tflops"] = max(out["mfma_bf16_32x32x16_tflops"], out["mfma_bf16_16x16x32_tflops"])
     return out
 
