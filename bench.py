@@ -507,8 +507,12 @@ def model_leg(torch, B, inputs, name, Bn, densities, steps, seed):
         gdt = time.perf_counter() - t0
         leg["hip_graph"] = {"ms_per_step": round(gdt / steps * 1e3, 3), "images_per_s": round(Bn * steps / gdt, 2)}
         out["dense" if r == 1.0 else f"density_{r}"] = leg
+    dense_flops = encoder_flops(shape, g, Bn, 1.0, 1.0, n)[0]
     for r in densities:
         out[f"density_{r}"]["speedup_over_dense"] = round(out["dense"]["ms_per_step"] / out[f"density_{r}"]["ms_per_step"], 3)
+        # what the speed-up would be if time were proportional to the algorithmic FLOPs
+        out[f"density_{r}"]["flop_ratio_dense_over_sparse"] = round(
+            dense_flops / encoder_flops(shape, g, Bn, r, r, B.ssam_keep_count(n, r))[0], 3)
     return out
 
 
@@ -668,7 +672,10 @@ def main():
         ddt, _, _ = timed(cfg_ld, cfg_gd, keep_dense, dsteps, 1, False)
         d_ms = ddt / dsteps * 1e3
         out["dense"] = {"ms_per_step": round(d_ms, 3), "images_per_s": round(Bn * dsteps / ddt, 3),
-                        "speedup_sparse_over_dense": round(d_ms / ms_per_step, 3)}
+                        "speedup_sparse_over_dense": round(d_ms / ms_per_step, 3),
+                        # what the speed-up would be if time were proportional to the algorithmic FLOPs
+                        "flop_ratio_dense_over_sparse": round(encoder_flops(shape, g, Bn, 1.0, 1.0, n)[0] /
+                                                              encoder_flops(shape, g, Bn, r, r, K)[0], 3)}
         # content-aware Stripe-Sort order (Sec. 4.1): per-image tables built from the scores inside the step
         nW_, S_ = (-(-g // shape.ws)) ** 2, shape.ws ** 2
         cl_c = B.make_cfg(Bn, g, shape.D, shape.heads, shape.Dm, shape.ws, 32, K, r, content_order=True)
@@ -696,7 +703,9 @@ def main():
             keep3 = torch.empty((Bn, K3), dtype=torch.int32, device=dev)
             tdt, _, _ = timed(cfg_l3, cfg_g3, keep3, dsteps, 1, False)
             out["density_0.3"] = {"ms_per_step": round(tdt / dsteps * 1e3, 3), "images_per_s": round(Bn * dsteps / tdt, 3),
-                                  "keep": K3, "speedup_over_dense": round(d_ms / (tdt / dsteps * 1e3), 3)}
+                                  "keep": K3, "speedup_over_dense": round(d_ms / (tdt / dsteps * 1e3), 3),
+                                  "flop_ratio_dense_over_sparse": round(encoder_flops(shape, g, Bn, 1.0, 1.0, n)[0] /
+                                                                        encoder_flops(shape, g, Bn, 0.3, 0.3, K3)[0], 3)}
 
     # ---- activation memory per density
     if not args.no_dense:
