@@ -469,7 +469,12 @@ gemm_bf16_nt_body(const bf16 *__restrict__ A, const bf16 *__restrict__ W, const 
                 for (int e = 0; e < 8; ++e) v[e] += o[e];
                 *reinterpret_cast<uint4 *>(C + (long)drow[pass] * ld.c + ncol) = pack_bf16x8(v);
             } else if (EPI == SSAM_EPI_BIAS_SCATTER) {
-                if (drow[pass] >= 0) *reinterpret_cast<uint4 *>(C + (long)drow[pass] * ld.c + ncol) = pack_bf16x8(v);
+                // (a mapped store is the qkv tensor: written once, read once by the attention kernel that follows; the
+                // non-temporal hint keeps it from displacing what the later kernels of the block want cached)
+                if (drow[pass] >= 0) {
+                    const uint4 pk_ = pack_bf16x8(v);
+                    __builtin_nontemporal_store(__builtin_bit_cast(u32x4, pk_), reinterpret_cast<u32x4 *>(C + (long)drow[pass] * ld.c + ncol));
+                }
             } else {
                 *reinterpret_cast<uint4 *>(C + (long)m * ld.c + ncol) = pack_bf16x8(v);
             }
